@@ -1,0 +1,131 @@
+/*
+ * sp_attn.h -- C ABI of the shared-prompt attention library for AMD MI355X (gfx950).
+ *
+ * The operation is the attention of Section 4.3 ("Shared-Prompt Attention") of
+ * "Periodic Asynchrony: An On-Policy Approach for Accelerating LLM Reinforcement
+ * Learning": one group's tokens are packed as [prompt | resp_1 | ... | resp_G]
+ * (modification 1 of that section), and the mask (modification 3) lets a prompt
+ * token attend causally to the prompt, and a token of response i attend to the
+ * whole prompt and causally to response i, never to another response.  The result
+ * equals G ordinary causal attentions over [prompt | resp_i] (closing paragraph of
+ * the section), with the prompt's key/value gradients summed over the G responses.
+ *
+ * Conventions common to every entry point
+ *   - Tensors are DEVICE pointers, row-major and contiguous, token-major:
+ *       q, o, d_o, dq : [T_total, n_q_heads,  head_dim]
+ *       k, v, dk, dv  : [T_total, n_kv_heads, head_dim]
+ *       lse           : [n_q_heads, T_total]  float32, natural log of
+ *                       sum over allowed keys of exp(softmax_scale * <q, k>)
+ *     Element type is bf16 (SP_BF16) or float32 (SP_F32, a plain-ALU debug path).
+ *     Base pointers must be 16-byte aligned.
+ *   - q head h reads kv head h / (n_q_heads / n_kv_heads) (contiguous blocks).
+ *   - q and k arrive already position-encoded: the restarted position ids of
+ *     modification 2 are applied by the caller before this call.
+ *   - Lengths (prompt_len, resp_lens[...]) are HOST integers and are consumed
+ *     before the call returns.  Zero-length responses and prompt_len == 0 are
+ *     legal; a group must hold at least one token.
+ *   - The caller owns all device memory including the workspace.  The library
+ *     never allocates, frees or synchronises; work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call
+ *     returns at once.  Outputs are overwritten, inputs are never modified.
+ *   - Every call returns sp_status.  On any error nothing has been enqueued and
+ *     sp_attn_last_error() describes the reason.
+ */
+#ifndef SP_ATTN_H
+#define SP_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SP_OK = 0,
+    SP_ERR_INVALID_ARG = 1,   /* null/misaligned pointer, negative length, empty group,
+                                 n_q_heads % n_kv_heads != 0, scale not finite or <= 0 */
+    SP_ERR_UNSUPPORTED = 2,   /* head_dim or dtype the kernels do not implement */
+    SP_ERR_WORKSPACE = 3,     /* workspace NULL or smaller than sp_attn_workspace_bytes() */
+    SP_ERR_DEVICE = 4         /* the HIP runtime reported a launch error */
+} sp_status;
+
+typedef enum {
+    SP_BF16 = 0,              /* bf16 tensors, bf16 MFMA contractions, fp32 softmax/accumulate;
+                                 head_dim must be 128 */
+    SP_F32 = 1                /* float32 tensors, plain-ALU debug path; head_dim 64 or 128 */
+} sp_dtype;
+
+/* Which kernel schedule the forward uses.  SP_SCHED_SHARED is the product path:
+ * wholly masked tiles are skipped and prompt key/value tiles are shared by the
+ * query tiles of all responses.  SP_SCHED_NAIVE_CAUSAL is a measurement baseline
+ * that visits every tile at or below the diagonal of the packed sequence and
+ * applies the mask element by element; its results are identical. */
+typedef enum { SP_SCHED_SHARED = 0, SP_SCHED_NAIVE_CAUSAL = 1 } sp_schedule;
+
+/* Bytes of device workspace a call needs (Section 4.3 has no counterpart: this is
+ * where the segment table and, for the backward, D = rowsum(dO * O) live).
+ * total_tokens = sum over groups of prompt_len + sum(resp_lens); total_responses =
+ * sum of G over groups.  Returns 0 for arguments no call would accept. */
+size_t sp_attn_workspace_bytes(int is_bwd, int64_t total_tokens, int32_t n_groups,
+                               int64_t total_responses, int32_t n_q_heads,
+                               int32_t n_kv_heads, int32_t head_dim, sp_dtype dtype);
+
+/* Forward for one group (Section 4.3, modifications 1 and 3): writes
+ * o [T, n_q_heads, head_dim] and lse [n_q_heads, T], T = prompt_len + sum(resp_lens).
+ * resp_lens: HOST array of G >= 0 entries (may be NULL when G == 0). */
+sp_status sp_attn_fwd(const void* q, const void* k, const void* v,
+                      void* o, float* lse,
+                      int32_t prompt_len, const int32_t* resp_lens, int32_t G,
+                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                      float softmax_scale, sp_dtype dtype,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward for one group: given o and lse from sp_attn_fwd and the upstream
+ * gradient d_o (all T rows, prompt rows included), overwrites dq, dk, dv with the
+ * exact gradient of sum(o * d_o).  The prompt rows of dk/dv accumulate the
+ * contributions of the later prompt rows and of every row of all G responses
+ * (the equivalence grad L_shared = sum_k grad L_k of Section 4.3); each kv head
+ * sums over the q heads that read it.  Deterministic: no atomics are used. */
+sp_status sp_attn_bwd(const void* q, const void* k, const void* v,
+                      const void* o, const float* lse, const void* d_o,
+                      void* dq, void* dk, void* dv,
+                      int32_t prompt_len, const int32_t* resp_lens, int32_t G,
+                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                      float softmax_scale, sp_dtype dtype,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Batched forms: n_groups independent groups packed back to back along the token
+ * axis (samples at their native lengths, no padding, as in Section 5).  Group g has
+ * prompt_lens[g] prompt tokens and Gs[g] responses whose lengths are the next Gs[g]
+ * entries of resp_lens_flat.  All three arrays are HOST memory.  Several weight
+ * sets (policy / old policy / reference, Section 4.2.1) are simply more groups.
+ * `schedule` selects SP_SCHED_SHARED or the naive baseline (forward only). */
+sp_status sp_attn_fwd_batched(const void* q, const void* k, const void* v,
+                              void* o, float* lse,
+                              int32_t n_groups, const int32_t* prompt_lens,
+                              const int32_t* Gs, const int32_t* resp_lens_flat,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                              float softmax_scale, sp_dtype dtype, sp_schedule schedule,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v,
+                              const void* o, const float* lse, const void* d_o,
+                              void* dq, void* dk, void* dv,
+                              int32_t n_groups, const int32_t* prompt_lens,
+                              const int32_t* Gs, const int32_t* resp_lens_flat,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                              float softmax_scale, sp_dtype dtype,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Text of the most recent error on the calling thread ("" if none).  The pointer
+ * refers to thread-local static storage; the caller must not free it. */
+const char* sp_attn_last_error(void);
+
+/* Library version, "major.minor". */
+const char* sp_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SP_ATTN_H */

@@ -1,0 +1,164 @@
+"""ctypes binding of libsp_attn.so.  Argument marshalling only: every step of the
+attention runs in the HIP kernels behind the C ABI declared in include/sp_attn.h.
+torch is used for device memory and streams, nothing else.  There is no CPU fallback:
+if the library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsp_attn.so")
+
+SP_OK = 0
+SP_ERR_INVALID_ARG, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_DEVICE = 1, 2, 3, 4
+SP_BF16, SP_F32 = 0, 1
+SP_SCHED_SHARED, SP_SCHED_NAIVE_CAUSAL = 0, 1
+
+EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
+           "sp_attn_bwd_batched", "sp_attn_last_error", "sp_attn_version")
+
+_lib = None
+
+
+class SpAttnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"sp_attn status {status}: {message}")
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree library, building it first only if it has never been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build_library
+        build_library(verbose=False)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    ip = ctypes.POINTER(ctypes.c_int32)
+    lib.sp_attn_workspace_bytes.restype = sz
+    lib.sp_attn_workspace_bytes.argtypes = [ctypes.c_int, i64, i32, i64, i32, i32, i32, ctypes.c_int]
+    lib.sp_attn_fwd.restype = ctypes.c_int
+    lib.sp_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i32, ip, i32, i32, i32, i32, f32, ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_bwd.restype = ctypes.c_int
+    lib.sp_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, i32, i32, i32, i32, f32,
+                                ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_fwd_batched.restype = ctypes.c_int
+    lib.sp_attn_fwd_batched.argtypes = [vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32, ctypes.c_int,
+                                        ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_bwd_batched.restype = ctypes.c_int
+    lib.sp_attn_bwd_batched.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32,
+                                        ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_last_error.restype = ctypes.c_char_p
+    lib.sp_attn_last_error.argtypes = []
+    lib.sp_attn_version.restype = ctypes.c_char_p
+    lib.sp_attn_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != SP_OK:
+        raise SpAttnError(status, load_library().sp_attn_last_error().decode())
+
+
+def _i32(xs: Sequence[int]):
+    arr = (ctypes.c_int32 * max(1, len(xs)))(*xs)
+    return arr
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return SP_BF16
+    if t.dtype == torch.float32:
+        return SP_F32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def workspace_bytes(is_bwd: bool, total_tokens: int, n_groups: int, total_responses: int, n_q_heads: int,
+                    n_kv_heads: int, head_dim: int, dtype_code: int) -> int:
+    return load_library().sp_attn_workspace_bytes(int(is_bwd), total_tokens, n_groups, total_responses, n_q_heads,
+                                                  n_kv_heads, head_dim, dtype_code)
+
+
+def _workspace(is_bwd, q, n_groups, n_resp, n_kv_heads, workspace):
+    T, Hq, d = q.shape
+    need = workspace_bytes(is_bwd, T, n_groups, n_resp, Hq, n_kv_heads, d, _dtype_code(q))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    return workspace
+
+
+def sp_attn_fwd(q, k, v, prompt_len: int, resp_lens: Sequence[int], softmax_scale: float,
+                o=None, lse=None, workspace=None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Forward for one group.  q [T,Hq,d]; k, v [T,Hkv,d] on the GPU.  Returns (o, lse)."""
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty(Hq, T, dtype=torch.float32, device=q.device) if lse is None else lse
+    workspace = _workspace(False, q, 1, len(resp_lens), Hkv, workspace)
+    _check(lib.sp_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), prompt_len,
+                           _i32(resp_lens), len(resp_lens), Hq, Hkv, d, softmax_scale, _dtype_code(q),
+                           workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return o, lse
+
+
+def sp_attn_bwd(q, k, v, o, lse, d_o, prompt_len: int, resp_lens: Sequence[int], softmax_scale: float,
+                dq=None, dk=None, dv=None, workspace=None, stream=None):
+    """Backward for one group.  Returns (dq, dk, dv)."""
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    workspace = _workspace(True, q, 1, len(resp_lens), Hkv, workspace)
+    _check(lib.sp_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
+                           dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), prompt_len, _i32(resp_lens),
+                           len(resp_lens), Hq, Hkv, d, softmax_scale, _dtype_code(q), workspace.data_ptr(),
+                           workspace.numel(), _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def sp_attn_fwd_batched(q, k, v, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int],
+                        softmax_scale: float, schedule: int = SP_SCHED_SHARED, o=None, lse=None, workspace=None,
+                        stream=None):
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty(Hq, T, dtype=torch.float32, device=q.device) if lse is None else lse
+    workspace = _workspace(False, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    _check(lib.sp_attn_fwd_batched(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                   len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d,
+                                   softmax_scale, _dtype_code(q), schedule, workspace.data_ptr(),
+                                   workspace.numel(), _stream_ptr(stream)))
+    return o, lse
+
+
+def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],
+                        resp_lens_flat: Sequence[int], softmax_scale: float, dq=None, dk=None, dv=None,
+                        workspace=None, stream=None):
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    workspace = _workspace(True, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    _check(lib.sp_attn_bwd_batched(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                   d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), len(prompt_lens),
+                                   _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
+                                   _dtype_code(q), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return dq, dk, dv

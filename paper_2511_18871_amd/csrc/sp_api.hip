@@ -1,0 +1,191 @@
+// C-ABI entry points of the shared-prompt attention library: argument validation,
+// segment-table construction and kernel dispatch.  See include/sp_attn.h for the contract.
+#include "../../include/sp_attn.h"
+#include "sp_common.hpp"
+#include "sp_launch.hpp"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+sp_status fail(sp_status code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+size_t table_words(int32_t n_groups, int64_t total_responses) {
+    return (size_t)sp::TAB_HEADER + (size_t)sp::TAB_GROUP_WORDS * n_groups + (size_t)total_responses + n_groups;
+}
+
+sp_status check_geometry(int32_t Hq, int32_t Hkv, int32_t d, float scale, sp_dtype dtype) {
+    if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0)
+        return fail(SP_ERR_INVALID_ARG, "n_q_heads=%d must be a positive multiple of n_kv_heads=%d", Hq, Hkv);
+    if (!std::isfinite(scale) || scale <= 0.f)
+        return fail(SP_ERR_INVALID_ARG, "softmax_scale must be finite and > 0");
+    if (dtype == SP_BF16) {
+        if (d != 128) return fail(SP_ERR_UNSUPPORTED, "bf16 path supports head_dim 128 only (got %d)", d);
+    } else if (dtype == SP_F32) {
+        if (d != 64 && d != 128) return fail(SP_ERR_UNSUPPORTED, "fp32 path supports head_dim 64 or 128 (got %d)", d);
+    } else {
+        return fail(SP_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    }
+    return SP_OK;
+}
+
+struct Layout {
+    std::vector<int32_t> words;       // the segment table
+    std::vector<int> group_tokens;
+    int64_t total_tokens = 0;
+    int64_t total_responses = 0;
+    int max_group_tokens = 0;
+};
+
+sp_status build_table(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
+                      const int32_t* resp_lens_flat, Layout& L) {
+    if (n_groups < 1) return fail(SP_ERR_INVALID_ARG, "n_groups must be >= 1");
+    if (!prompt_lens || !Gs) return fail(SP_ERR_INVALID_ARG, "prompt_lens / Gs is NULL");
+    int64_t nresp = 0;
+    for (int g = 0; g < n_groups; ++g) {
+        if (Gs[g] < 0) return fail(SP_ERR_INVALID_ARG, "group %d: G=%d is negative", g, Gs[g]);
+        nresp += Gs[g];
+    }
+    if (nresp > 0 && !resp_lens_flat) return fail(SP_ERR_INVALID_ARG, "resp_lens is NULL but G > 0");
+    if (nresp > (int64_t)1 << 28) return fail(SP_ERR_INVALID_ARG, "too many responses");
+    L.total_responses = nresp;
+    L.words.assign(table_words(n_groups, nresp), 0);
+    L.group_tokens.resize(n_groups);
+    int64_t tok = 0, r = 0;
+    size_t roff = (size_t)sp::TAB_HEADER + (size_t)sp::TAB_GROUP_WORDS * n_groups;
+    for (int g = 0; g < n_groups; ++g) {
+        if (prompt_lens[g] < 0) return fail(SP_ERR_INVALID_ARG, "group %d: prompt_len is negative", g);
+        int64_t tg = prompt_lens[g];
+        int32_t* e = &L.words[sp::TAB_HEADER + sp::TAB_GROUP_WORDS * g];
+        e[0] = (int32_t)tok; e[1] = prompt_lens[g]; e[3] = (int32_t)roff; e[4] = Gs[g];
+        L.words[roff++] = prompt_lens[g];
+        for (int i = 0; i < Gs[g]; ++i, ++r) {
+            if (resp_lens_flat[r] < 0) return fail(SP_ERR_INVALID_ARG, "group %d: response %d has negative length", g, i);
+            tg += resp_lens_flat[r];
+            if (tg > 0x7fff0000LL) return fail(SP_ERR_INVALID_ARG, "group %d holds too many tokens", g);
+            L.words[roff++] = (int32_t)tg;
+        }
+        if (tg < 1) return fail(SP_ERR_INVALID_ARG, "group %d is empty (needs at least one token)", g);
+        e[2] = (int32_t)tg;
+        L.group_tokens[g] = (int)tg;
+        if (tg > L.max_group_tokens) L.max_group_tokens = (int)tg;
+        tok += tg;
+        if (tok > 0x7fff0000LL) return fail(SP_ERR_INVALID_ARG, "total token count exceeds the int32 range");
+    }
+    L.total_tokens = tok;
+    L.words[0] = n_groups; L.words[1] = (int32_t)tok; L.words[2] = (int32_t)L.words.size();
+    return SP_OK;
+}
+
+sp_status run(bool bwd, const void* q, const void* k, const void* v, const void* o, const float* lse,
+              const void* d_o, void* o_out, float* lse_out, void* dq, void* dk, void* dv,
+              int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+              int32_t Hq, int32_t Hkv, int32_t d, float scale, sp_dtype dtype, sp_schedule schedule,
+              void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    sp_status st = check_geometry(Hq, Hkv, d, scale, dtype);
+    if (st != SP_OK) return st;
+    if (schedule != SP_SCHED_SHARED && schedule != SP_SCHED_NAIVE_CAUSAL)
+        return fail(SP_ERR_INVALID_ARG, "unknown schedule %d", (int)schedule);
+    const void* ptrs[] = {q, k, v, bwd ? o : o_out, bwd ? (const void*)lse : (const void*)lse_out,
+                          bwd ? d_o : q, bwd ? dq : q, bwd ? dk : q, bwd ? dv : q};
+    for (const void* p : ptrs) {
+        if (!p) return fail(SP_ERR_INVALID_ARG, "a tensor pointer is NULL");
+        if (misaligned(p)) return fail(SP_ERR_INVALID_ARG, "tensor pointer %p is not 16-byte aligned", p);
+    }
+    Layout L;
+    st = build_table(n_groups, prompt_lens, Gs, resp_lens_flat, L);
+    if (st != SP_OK) return st;
+    const size_t need = sp_attn_workspace_bytes(bwd, L.total_tokens, n_groups, L.total_responses, Hq, Hkv, d, dtype);
+    if (!workspace || misaligned(workspace) || workspace_bytes < need)
+        return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
+                    workspace_bytes, need);
+
+    hipStream_t s = (hipStream_t)stream;
+    sp::Problem p{};
+    p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse; p.d_o = d_o;
+    p.o_out = o_out; p.lse_out = lse_out; p.dq = dq; p.dk = dk; p.dv = dv;
+    p.tab = (const int*)workspace;
+    p.Dbuf = (float*)((char*)workspace + align256(L.words.size() * 4));
+    p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
+    p.Hq = Hq; p.Hkv = Hkv; p.head_dim = d; p.scale = scale;
+    p.naive = schedule == SP_SCHED_NAIVE_CAUSAL;
+    p.host_group_tokens = L.group_tokens.data();
+
+    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    if (e == hipSuccess) {
+        if (dtype == SP_BF16) e = bwd ? sp::launch_bwd_bf16(p, s) : sp::launch_fwd_bf16(p, s);
+        else e = bwd ? sp::launch_bwd_f32(p, s) : sp::launch_fwd_f32(p, s);
+    }
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
+    return SP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sp_attn_workspace_bytes(int is_bwd, int64_t total_tokens, int32_t n_groups, int64_t total_responses,
+                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, sp_dtype dtype) {
+    (void)n_kv_heads; (void)head_dim; (void)dtype;
+    if (total_tokens < 1 || n_groups < 1 || total_responses < 0 || n_q_heads < 1) return 0;
+    size_t bytes = align256(table_words(n_groups, total_responses) * 4);
+    if (is_bwd) bytes += align256((size_t)n_q_heads * (size_t)total_tokens * 4);
+    return bytes;
+}
+
+sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int32_t prompt_len,
+                      const int32_t* resp_lens, int32_t G, int32_t n_q_heads, int32_t n_kv_heads,
+                      int32_t head_dim, float softmax_scale, sp_dtype dtype, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, 1, &prompt_len, &G,
+               resp_lens, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, workspace,
+               workspace_bytes, stream);
+}
+
+sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                      const void* d_o, void* dq, void* dk, void* dv, int32_t prompt_len, const int32_t* resp_lens,
+                      int32_t G, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                      sp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, 1, &prompt_len, &G, resp_lens, n_q_heads,
+               n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, workspace, workspace_bytes, stream);
+}
+
+sp_status sp_attn_fwd_batched(const void* q, const void* k, const void* v, void* o, float* lse, int32_t n_groups,
+                              const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                              sp_dtype dtype, sp_schedule schedule, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, n_groups, prompt_lens,
+               Gs, resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, schedule, workspace,
+               workspace_bytes, stream);
+}
+
+sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                              const void* d_o, void* dq, void* dk, void* dv, int32_t n_groups,
+                              const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                              sp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs, resp_lens_flat,
+               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, workspace, workspace_bytes,
+               stream);
+}
+
+const char* sp_attn_last_error(void) { return g_err; }
+const char* sp_attn_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,185 @@
+// Shared device-side definitions for the shared-prompt attention kernels (gfx950 only).
+//
+// Packed layout and mask follow Section 4.3 of the paper: a group is
+// [prompt | resp_1 | ... | resp_G]; query t may attend key s iff s <= t and
+// (s is a prompt token or s lies in t's own response).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------
+// Segment table (int32 words, device memory, written by sp_upload_table):
+//   [0] n_groups   [1] total_tokens   [2] table_words   [3] reserved
+//   group g at 4 + 6*g : { tok_base, prompt_len, T_g, roff_idx, G, reserved }
+//   roff_idx points at G+1 group-local offsets: roff[0] = prompt_len,
+//   roff[i+1] = roff[i] + len(resp_i), roff[G] = T_g.
+// ---------------------------------------------------------------------------
+constexpr int TAB_HEADER = 4;
+constexpr int TAB_GROUP_WORDS = 6;
+constexpr int TAB_CHUNK_WORDS = 960;   // words carried by one upload launch (kernarg limit 4 KB)
+
+struct TabChunk { int32_t w[TAB_CHUNK_WORDS]; };
+
+struct GroupDesc {
+    int tok_base;       // first packed token of the group
+    int Lp;             // prompt length
+    int Tg;             // tokens in the group
+    int G;              // number of responses
+    const int* roff;    // G+1 group-local response offsets
+};
+
+__device__ __forceinline__ GroupDesc load_group(const int* __restrict__ tab, int g) {
+    const int* e = tab + TAB_HEADER + TAB_GROUP_WORDS * g;
+    GroupDesc d;
+    d.tok_base = e[0]; d.Lp = e[1]; d.Tg = e[2]; d.roff = tab + e[3]; d.G = e[4];
+    return d;
+}
+
+// Start of the segment that owns group-local token t: 0 for a prompt token, the first
+// token of its response otherwise.  Requires 0 <= t < Tg.  With this value the mask is
+//   allowed(t, s) = (s <= t) && (s < Lp || s >= seg_start(t)).
+__device__ __forceinline__ int seg_start(const GroupDesc& d, int t) {
+    if (t < d.Lp) return 0;
+    int lo = 0, hi = d.G;              // invariant: roff[lo] <= t, (hi == G or roff[hi] > t)
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (d.roff[mid] <= t) lo = mid; else hi = mid;
+    }
+    return d.roff[lo];
+}
+
+// One past the last token of the segment that owns t (prompt: Lp).
+__device__ __forceinline__ int seg_end(const GroupDesc& d, int t) {
+    if (t < d.Lp) return d.Lp;
+    int lo = 0, hi = d.G;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (d.roff[mid] <= t) lo = mid; else hi = mid;
+    }
+    return d.roff[lo + 1];
+}
+
+// Work-tile lookup: tiles of `bm` rows are numbered group by group; inside a group the
+// LAST tile comes first (response tiles and late prompt tiles carry the most work, so
+// launch order is roughly longest-first).  Returns the group and the tile's first row.
+__device__ __forceinline__ void find_tile(const int* __restrict__ tab, int tile, int bm,
+                                          int& g_out, int& t0_out) {
+    const int ng = tab[0];
+    int g = 0, base = 0;
+    for (; g < ng; ++g) {
+        const int Tg = tab[TAB_HEADER + TAB_GROUP_WORDS * g + 2];
+        const int nt = (Tg + bm - 1) / bm;
+        if (tile < base + nt) {
+            g_out = g;
+            t0_out = (nt - 1 - (tile - base)) * bm;
+            return;
+        }
+        base += nt;
+    }
+    g_out = -1; t0_out = 0;
+}
+
+// Map a flat block index to (tile, q head) so that the blocks an XCD receives
+// (blocks are dealt round-robin over the 8 XCDs, each with a private L2) share one
+// kv head, and q heads of the same tile sit next to each other.
+// Returns false when the block has no work.
+__device__ __forceinline__ bool decode_item(int bid, int n_tiles, int Hq, int Hkv,
+                                            int& tile, int& head) {
+    const int rep = Hq / Hkv;
+    const int per_kv = n_tiles * rep;          // items of one kv head
+    if (Hkv % 8 == 0) {
+        const int x = bid & 7, j = bid >> 3;
+        const int kv_per_x = Hkv >> 3;
+        const int hr = j % rep;
+        const int rest = j / rep;
+        const int kvl = rest % kv_per_x;
+        tile = rest / kv_per_x;
+        head = (x + 8 * kvl) * rep + hr;
+        return tile < n_tiles;
+    }
+    if (8 % Hkv == 0) {
+        const int nx = 8 / Hkv;                // XCDs that share one kv head
+        const int x = bid & 7, j = bid >> 3;
+        const int kvh = x / nx, sub = x % nx;
+        const int it = j * nx + sub;
+        if (it >= per_kv) return false;
+        tile = it / rep;
+        head = kvh * rep + it % rep;
+        return true;
+    }
+    tile = bid / Hq;
+    head = bid % Hq;
+    return tile < n_tiles;
+}
+
+__host__ __device__ inline int grid_for_items(int n_tiles, int Hq, int Hkv) {
+    const int rep = Hq / Hkv;
+    if (Hkv % 8 == 0) return 8 * (n_tiles * rep * (Hkv / 8));
+    if (8 % Hkv == 0) { const int nx = 8 / Hkv; return 8 * ((n_tiles * rep + nx - 1) / nx); }
+    return n_tiles * Hq;
+}
+
+// ---------------------------------------------------------------------------
+// LDS tiles: rows of 128 bf16 (256 B = 16 granules of 16 B).  Granule g of row r is
+// stored at granule slot g ^ swz(r).  swz permutes 0..15 over 16 consecutive rows
+// (conflict-free b128 reads of one granule column by 16 rows) and its two high bits
+// differ over 4 consecutive rows (conflict-free transposed b64 reads of a 4-row x
+// 4-granule block).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+__device__ __forceinline__ int tile_off(int row, int granule) {   // byte offset
+    return row * 256 + ((granule ^ swz(row)) << 4);
+}
+
+typedef __attribute__((address_space(3))) char lds_char;
+
+__device__ __forceinline__ bf16x8 lds_read_row8(const char* tile, int row, int granule) {
+    return *reinterpret_cast<const bf16x8*>(tile + tile_off(row, granule));
+}
+
+// Transposed read feeding an MFMA operand whose in-lane (contraction) index runs over
+// tile ROWS: the lane receives rows row4 .. row4+3 at column col (one bf16 each).
+// Lanes of a 16-lane group must pass: row = row4 + (j >> 2), col4 = colbase + 4*(j & 3)
+// with j = lane & 15; lane j then receives column colbase + j.
+__device__ __forceinline__ s16x4 lds_read_tr4(const char* tile, int row, int col4) {
+    const char* p = tile + tile_off(row, col4 >> 3) + ((col4 & 4) << 1);
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(p));
+}
+
+__device__ __forceinline__ bf16x8 cat4(s16x4 a, s16x4 b) {
+    s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Round 8 floats to bf16 (round-to-nearest-even, hardware v_cvt_pk_bf16_f32).
+__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
+                                        float a4, float a5, float a6, float a7) {
+    bf16x8 r;
+    r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+    r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
+    return r;
+}
+
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+}  // namespace sp

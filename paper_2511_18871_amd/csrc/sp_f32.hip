@@ -1,0 +1,270 @@
+// float32 plain-ALU debug path of shared-prompt attention, the segment-table upload
+// and the backward preprocess D = rowsum(dO * O).
+//
+// The debug kernels give one wavefront a single (row, head) or (key, kv head) and walk
+// the allowed keys / rows of the Section 4.3 mask in chunks of 64, one per lane.  No
+// MFMA, no LDS: they exist to cross-check the MFMA path and to serve float32 callers.
+#include "sp_common.hpp"
+#include "sp_launch.hpp"
+
+namespace sp {
+namespace {
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// group that owns packed token tok
+__device__ __forceinline__ int find_group(const int* __restrict__ tab, int tok) {
+    const int ng = tab[0];
+    int g = 0;
+    while (g + 1 < ng && tab[TAB_HEADER + TAB_GROUP_WORDS * (g + 1)] <= tok) ++g;
+    return g;
+}
+
+__global__ void upload_table_kernel(TabChunk chunk, int* __restrict__ dst, int offset, int count) {
+    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[offset + i] = chunk.w[i];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, const T* __restrict__ o,
+                                                     float* __restrict__ D, int64_t T_total, int Hq, int dh) {
+    const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int l = threadIdx.x & 63;
+    if (gw >= T_total * Hq) return;
+    const int64_t tok = gw / Hq;
+    const int h = (int)(gw % Hq);
+    const T* a = d_o + gw * dh;
+    const T* b = o + gw * dh;
+    float acc = 0.f;
+    for (int i = l; i < dh; i += 64) acc += (float)a[i] * (float)b[i];
+    acc = wave_sum(acc);
+    if (l == 0) D[(int64_t)h * T_total + tok] = acc;
+}
+
+template <int DH>
+__device__ __forceinline__ float dot_row(const float* __restrict__ x, const float* __restrict__ y) {
+    float acc = 0.f;
+#pragma unroll 8
+    for (int i = 0; i < DH; ++i) acc = __builtin_fmaf(x[i], y[i], acc);
+    return acc;
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
+                                                      const float* __restrict__ v, float* __restrict__ o,
+                                                      float* __restrict__ lse, const int* __restrict__ tab,
+                                                      int Hq, int Hkv, float scale) {
+    constexpr int PER = DH / 64;
+    const int64_t T_total = tab[1];
+    const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int l = threadIdx.x & 63;
+    if (gw >= T_total * Hq) return;
+    const int tok = (int)(gw / Hq), h = (int)(gw % Hq);
+    const GroupDesc gd = load_group(tab, find_group(tab, tok));
+    const int t = tok - gd.tok_base;
+    const int st = seg_start(gd, t);
+    const int kvh = h / (Hq / Hkv);
+    const float* qrow = q + ((int64_t)tok * Hq + h) * DH;
+    const float* kb = k + ((int64_t)gd.tok_base * Hkv + kvh) * DH;
+    const float* vb = v + ((int64_t)gd.tok_base * Hkv + kvh) * DH;
+    const int64_t kvs = (int64_t)Hkv * DH;
+
+    float m = -INFINITY, lsum = 0.f, acc[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+    for (int s0 = 0; s0 <= t; s0 += 64) {
+        if (s0 >= gd.Lp && s0 + 64 <= st) continue;        // wholly inside other responses
+        const int s = s0 + l;
+        const bool ok = s <= t && (s < gd.Lp || s >= st);
+        const float sc = ok ? scale * dot_row<DH>(qrow, kb + (int64_t)s * kvs) : -INFINITY;
+        const float mnew = fmaxf(m, wave_max(sc));
+        if (mnew == -INFINITY) continue;
+        const float alpha = expf(m - mnew);
+        const float p = ok ? expf(sc - mnew) : 0.f;
+        lsum = lsum * alpha + wave_sum(p);
+        m = mnew;
+        const int nk = min(64, t + 1 - s0);
+#pragma unroll
+        for (int e = 0; e < PER; ++e) acc[e] *= alpha;
+        for (int jj = 0; jj < nk; ++jj) {
+            const float pj = __shfl(p, jj, 64);
+            const float* vr = vb + (int64_t)(s0 + jj) * kvs;
+#pragma unroll
+            for (int e = 0; e < PER; ++e) acc[e] = __builtin_fmaf(pj, vr[l + 64 * e], acc[e]);
+        }
+    }
+    float* orow = o + ((int64_t)tok * Hq + h) * DH;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) orow[l + 64 * e] = acc[e] / lsum;
+    if (l == 0) lse[(int64_t)h * T_total + tok] = m + logf(lsum);
+}
+
+// dQ[t,h] = scale * sum_s dS[t,s] K[s],  dS = P * (dP - D)
+template <int DH>
+__global__ __launch_bounds__(256) void bwd_dq_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
+                                                         const float* __restrict__ v, const float* __restrict__ d_o,
+                                                         const float* __restrict__ lse, const float* __restrict__ D,
+                                                         float* __restrict__ dq, const int* __restrict__ tab,
+                                                         int Hq, int Hkv, float scale) {
+    constexpr int PER = DH / 64;
+    const int64_t T_total = tab[1];
+    const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int l = threadIdx.x & 63;
+    if (gw >= T_total * Hq) return;
+    const int tok = (int)(gw / Hq), h = (int)(gw % Hq);
+    const GroupDesc gd = load_group(tab, find_group(tab, tok));
+    const int t = tok - gd.tok_base;
+    const int st = seg_start(gd, t);
+    const int kvh = h / (Hq / Hkv);
+    const float* qrow = q + ((int64_t)tok * Hq + h) * DH;
+    const float* gorow = d_o + ((int64_t)tok * Hq + h) * DH;
+    const float* kb = k + ((int64_t)gd.tok_base * Hkv + kvh) * DH;
+    const float* vb = v + ((int64_t)gd.tok_base * Hkv + kvh) * DH;
+    const int64_t kvs = (int64_t)Hkv * DH;
+    const float L = lse[(int64_t)h * T_total + tok];
+    const float Dt = D[(int64_t)h * T_total + tok];
+
+    float acc[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+    for (int s0 = 0; s0 <= t; s0 += 64) {
+        if (s0 >= gd.Lp && s0 + 64 <= st) continue;
+        const int s = s0 + l;
+        const bool ok = s <= t && (s < gd.Lp || s >= st);
+        float ds = 0.f;
+        if (ok) {
+            const float p = expf(scale * dot_row<DH>(qrow, kb + (int64_t)s * kvs) - L);
+            ds = p * (dot_row<DH>(gorow, vb + (int64_t)s * kvs) - Dt);
+        }
+        const int nk = min(64, t + 1 - s0);
+        for (int jj = 0; jj < nk; ++jj) {
+            const float dj = __shfl(ds, jj, 64);
+            const float* kr = kb + (int64_t)(s0 + jj) * kvs;
+#pragma unroll
+            for (int e = 0; e < PER; ++e) acc[e] = __builtin_fmaf(dj, kr[l + 64 * e], acc[e]);
+        }
+    }
+    float* out = dq + ((int64_t)tok * Hq + h) * DH;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) out[l + 64 * e] = scale * acc[e];
+}
+
+// dK[s,g] = scale * sum_{h in g} sum_t dS[t,s] Q[t,h];  dV[s,g] = sum_{h in g} sum_t P[t,s] dO[t,h].
+// The rows that see key s are contiguous: [s, Tg) for a prompt key (later prompt rows and
+// every row of every response), [s, end of its response) otherwise.
+template <int DH>
+__global__ __launch_bounds__(256) void bwd_dkdv_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
+                                                           const float* __restrict__ v, const float* __restrict__ d_o,
+                                                           const float* __restrict__ lse, const float* __restrict__ D,
+                                                           float* __restrict__ dk, float* __restrict__ dv,
+                                                           const int* __restrict__ tab, int Hq, int Hkv, float scale) {
+    constexpr int PER = DH / 64;
+    const int64_t T_total = tab[1];
+    const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int l = threadIdx.x & 63;
+    if (gw >= T_total * Hkv) return;
+    const int tok = (int)(gw / Hkv), kvh = (int)(gw % Hkv);
+    const GroupDesc gd = load_group(tab, find_group(tab, tok));
+    const int s = tok - gd.tok_base;
+    const int row_end = s < gd.Lp ? gd.Tg : seg_end(gd, s);
+    const int rep = Hq / Hkv;
+    const float* krow = k + ((int64_t)tok * Hkv + kvh) * DH;
+    const float* vrow = v + ((int64_t)tok * Hkv + kvh) * DH;
+
+    float ak[PER], av[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) { ak[e] = 0.f; av[e] = 0.f; }
+    for (int hr = 0; hr < rep; ++hr) {
+        const int h = kvh * rep + hr;
+        for (int r0 = s; r0 < row_end; r0 += 64) {
+            const int t = r0 + l;
+            float p = 0.f, ds = 0.f;
+            if (t < row_end) {
+                const int64_t row = ((int64_t)(gd.tok_base + t) * Hq + h) * DH;
+                const int64_t sidx = (int64_t)h * T_total + gd.tok_base + t;
+                p = expf(scale * dot_row<DH>(q + row, krow) - lse[sidx]);
+                ds = p * (dot_row<DH>(d_o + row, vrow) - D[sidx]);
+            }
+            const int nr = min(64, row_end - r0);
+            for (int jj = 0; jj < nr; ++jj) {
+                const float pj = __shfl(p, jj, 64), dj = __shfl(ds, jj, 64);
+                const int64_t row = ((int64_t)(gd.tok_base + r0 + jj) * Hq + h) * DH;
+#pragma unroll
+                for (int e = 0; e < PER; ++e) {
+                    av[e] = __builtin_fmaf(pj, d_o[row + l + 64 * e], av[e]);
+                    ak[e] = __builtin_fmaf(dj, q[row + l + 64 * e], ak[e]);
+                }
+            }
+        }
+    }
+    float* okr = dk + ((int64_t)tok * Hkv + kvh) * DH;
+    float* ovr = dv + ((int64_t)tok * Hkv + kvh) * DH;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) { okr[l + 64 * e] = scale * ak[e]; ovr[l + 64 * e] = av[e]; }
+}
+
+inline int blocks_for_waves(int64_t waves) { return (int)((waves + 3) / 4); }
+
+}  // namespace
+
+hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s) {
+    for (int off = 0; off < n_words; off += TAB_CHUNK_WORDS) {
+        TabChunk c;
+        const int n = n_words - off < TAB_CHUNK_WORDS ? n_words - off : TAB_CHUNK_WORDS;
+        for (int i = 0; i < n; ++i) c.w[i] = host_words[off + i];
+        for (int i = n; i < TAB_CHUNK_WORDS; ++i) c.w[i] = 0;
+        hipLaunchKernelGGL(upload_table_kernel, dim3(1), dim3(256), 0, s, c, dev_tab, off, n);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
+    const int grid = blocks_for_waves(p.total_tokens * p.Hq);
+    if (f32)
+        hipLaunchKernelGGL(rowsum_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)p.d_o,
+                           (const float*)p.o, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
+    else
+        hipLaunchKernelGGL(rowsum_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)p.d_o,
+                           (const __bf16*)p.o, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_f32(const Problem& p, hipStream_t s) {
+    const int grid = blocks_for_waves(p.total_tokens * p.Hq);
+    if (p.head_dim == 64)
+        hipLaunchKernelGGL(fwd_f32_kernel<64>, dim3(grid), dim3(256), 0, s, (const float*)p.q, (const float*)p.k,
+                           (const float*)p.v, (float*)p.o_out, p.lse_out, p.tab, p.Hq, p.Hkv, p.scale);
+    else
+        hipLaunchKernelGGL(fwd_f32_kernel<128>, dim3(grid), dim3(256), 0, s, (const float*)p.q, (const float*)p.k,
+                           (const float*)p.v, (float*)p.o_out, p.lse_out, p.tab, p.Hq, p.Hkv, p.scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_f32(const Problem& p, hipStream_t s) {
+    hipError_t e = launch_rowsum(p, true, s);
+    if (e != hipSuccess) return e;
+    const int gq = blocks_for_waves(p.total_tokens * p.Hq);
+    const int gk = blocks_for_waves(p.total_tokens * p.Hkv);
+#define SP_F32_BWD(DH)                                                                                      \
+    hipLaunchKernelGGL(bwd_dq_f32_kernel<DH>, dim3(gq), dim3(256), 0, s, (const float*)p.q, (const float*)p.k, \
+                       (const float*)p.v, (const float*)p.d_o, p.lse, p.Dbuf, (float*)p.dq, p.tab, p.Hq,   \
+                       p.Hkv, p.scale);                                                                    \
+    hipLaunchKernelGGL(bwd_dkdv_f32_kernel<DH>, dim3(gk), dim3(256), 0, s, (const float*)p.q,              \
+                       (const float*)p.k, (const float*)p.v, (const float*)p.d_o, p.lse, p.Dbuf,           \
+                       (float*)p.dk, (float*)p.dv, p.tab, p.Hq, p.Hkv, p.scale);
+    if (p.head_dim == 64) { SP_F32_BWD(64) } else { SP_F32_BWD(128) }
+#undef SP_F32_BWD
+    return hipGetLastError();
+}
+
+}  // namespace sp

@@ -1,0 +1,38 @@
+// Internal launcher interface between the C-ABI layer (sp_api.hip) and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sp {
+
+struct Problem {
+    const void* q; const void* k; const void* v;
+    const void* o; const float* lse; const void* d_o;     // backward inputs (o also fwd output)
+    void* o_out; float* lse_out;                          // forward outputs
+    void* dq; void* dk; void* dv;                         // backward outputs
+    const int* tab;                                       // segment table (device)
+    float* Dbuf;                                          // [Hq, T_total] rowsum(dO*O) (device)
+    int n_groups;
+    int64_t total_tokens;
+    int max_group_tokens;
+    int Hq, Hkv, head_dim;
+    float scale;
+    int naive;                                            // forward: naive packed-causal schedule
+    // host copies of the per-group token counts, for grid sizing
+    const int* host_group_tokens;
+};
+
+hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s);
+hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s);
+hipError_t launch_fwd_f32(const Problem& p, hipStream_t s);
+hipError_t launch_bwd_f32(const Problem& p, hipStream_t s);
+hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s);
+hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s);
+
+inline int count_tiles(const Problem& p, int bm) {
+    int n = 0;
+    for (int g = 0; g < p.n_groups; ++g) n += (p.host_group_tokens[g] + bm - 1) / bm;
+    return n;
+}
+
+}  // namespace sp
