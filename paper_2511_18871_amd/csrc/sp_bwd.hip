@@ -1,5 +1,445 @@
+// Backward shared-prompt attention, bf16 MFMA path (gfx950).  Two deterministic passes
+// after D = rowsum(dO * O):
+//
+//  dq pass   -- a workgroup owns a tile of query rows (like the forward) and streams the
+//               keys that those rows may see: S^T = K Q^T, dP^T = V dO^T,
+//               dS^T = P^T * (dP^T - D), dQ^T += K^T dS^T.
+//  dkdv pass -- a workgroup owns a tile of keys of one kv head and streams every query
+//               row that sees them, for each q head of the kv head: for a PROMPT key tile
+//               that is the later prompt rows and all rows of all G responses, which is
+//               where the prompt's dK/dV accumulate over the responses (Section 4.3,
+//               grad L_shared = sum_k grad L_k).  S = Q K^T, dP = dO V^T,
+//               dV^T += dO^T P, dK^T += Q^T dS.  Accumulation stays in registers, so no
+//               atomics are needed and results are bitwise repeatable.
+//
+// The S/dP recomputation runs in both passes (7 contractions instead of 5); in exchange
+// neither pass exchanges dS between lanes or accumulates through memory.
 #include "sp_common.hpp"
 #include "sp_launch.hpp"
+
 namespace sp {
-hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) { return hipErrorNotSupported; }
+namespace {
+
+constexpr int TILE_BYTES = 64 * 256;   // 64 rows x 128 bf16
+
+struct BwdArgs {
+    const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* d_o;
+    const float* lse; const float* D;
+    __bf16* dq; __bf16* dk; __bf16* dv;
+    const int* tab;
+    int n_tiles, Hq, Hkv;
+    float scale, c;      // c = scale * log2(e)
+};
+
+// ------------------------------------------------------------------------------------
+// dq pass
+// ------------------------------------------------------------------------------------
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
+    constexpr int BM = 32 * NW, NT = 64 * NW, BN = 64;
+    constexpr int GR = (BN * 16) / NT;
+    __shared__ __attribute__((aligned(1024))) char lds[2 * TILE_BYTES];
+    char* ldsK = lds;
+    char* ldsV = lds + TILE_BYTES;
+
+    int tile, head;
+    if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
+    int g, t0;
+    find_tile(a.tab, tile, BM, g, t0);
+    if (g < 0) return;
+    const GroupDesc gd = load_group(a.tab, g);
+    const int Lp = gd.Lp, Tg = gd.Tg;
+    const int64_t T_total = a.tab[1];
+
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int c = l & 31, hh = l >> 5, j = l & 15, c16 = (l >> 4) & 1;
+
+    const int t = t0 + 32 * w + c;
+    const bool valid = t < Tg;
+    const int tm = valid ? t : -1;
+    const int st = valid ? seg_start(gd, t) : 0;
+    const int tw0 = t0 + 32 * w;
+    const bool wave_valid = tw0 < Tg;
+    const int tw1 = min(tw0 + 31, Tg - 1);
+    const int st_first = wave_valid ? seg_start(gd, tw0) : 0;
+    const int st_last = wave_valid ? seg_start(gd, tw1) : 0;
+
+    bf16x8 qreg[8], goreg[8];
+    float Lq = 0.f, Dq = 0.f;
+    {
+        const int64_t row = ((int64_t)(gd.tok_base + (valid ? t : 0)) * a.Hq + head) * 128 + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            bf16x8 x = *reinterpret_cast<const bf16x8*>(a.q + row + 16 * ks);
+            bf16x8 y = *reinterpret_cast<const bf16x8*>(a.d_o + row + 16 * ks);
+            if (!valid) { x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0}; y = x; }
+            qreg[ks] = x; goreg[ks] = y;
+        }
+        if (valid) {
+            Lq = a.lse[(int64_t)head * T_total + gd.tok_base + t] * LOG2E;
+            Dq = a.D[(int64_t)head * T_total + gd.tok_base + t];
+        }
+    }
+
+    const int t1 = min(t0 + BM, Tg);
+    int n1 = (min(Lp, t1) + BN - 1) / BN, k2b = n1, k2e = n1;
+    if (t1 > Lp) {
+        const int b2 = seg_start(gd, max(t0, Lp));
+        k2b = max(n1, b2 / BN);
+        k2e = (t1 + BN - 1) / BN;
+    }
+    const int total = n1 + (k2e - k2b);
+
+    const int kvh = head / (a.Hq / a.Hkv);
+    const int64_t kv_stride = (int64_t)a.Hkv * 128;
+    const __bf16* kbase = a.k + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
+    const __bf16* vbase = a.v + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
+
+    i32x4 kpre[GR], vpre[GR];
+    auto load_regs = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < GR; ++i) {
+            const int gid = tid + NT * i;
+            const int row = gid >> 4, gr = gid & 15;
+            const int s = kt * BN + row;
+            i32x4 kk = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+            if (s < Tg) {
+                kk = *reinterpret_cast<const i32x4*>(kbase + (int64_t)s * kv_stride + gr * 8);
+                vv = *reinterpret_cast<const i32x4*>(vbase + (int64_t)s * kv_stride + gr * 8);
+            }
+            kpre[i] = kk; vpre[i] = vv;
+        }
+    };
+    auto store_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < GR; ++i) {
+            const int gid = tid + NT * i;
+            const int row = gid >> 4, gr = gid & 15;
+            *reinterpret_cast<i32x4*>(ldsK + tile_off(row, gr)) = kpre[i];
+            *reinterpret_cast<i32x4*>(ldsV + tile_off(row, gr)) = vpre[i];
+        }
+    };
+    auto tile_at = [&](int it) { return it < n1 ? it : k2b + (it - n1); };
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+    const float cs = a.c;
+
+    if (total > 0) load_regs(tile_at(0));
+    for (int it = 0; it < total; ++it) {
+        const int kt = tile_at(it);
+        __syncthreads();
+        store_lds();
+        __syncthreads();
+        if (it + 1 < total) load_regs(tile_at(it + 1));
+
+        const int s0 = kt * BN;
+        const bool skip = !wave_valid || s0 > tw1 || (s0 >= Lp && s0 + BN <= st_first);
+        if (skip) continue;
+
+        f32x16 sacc[2], pacc[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 A = lds_read_row8(ldsK, 32 * kb + c, 2 * ks + hh);
+                sacc[kb] = mfma32(A, qreg[ks], sacc[kb]);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 A = lds_read_row8(ldsV, 32 * kb + c, 2 * ks + hh);
+                pacc[kb] = mfma32(A, goreg[ks], pacc[kb]);
+            }
+        }
+        const bool full = (s0 + BN - 1 <= tw0) && (s0 + BN <= Lp || s0 >= st_last);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], cs, -Lq));
+                if (!full) {
+                    const int key = s0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const bool ok = key <= tm && (key < Lp || key >= st);
+                    p = ok ? p : 0.f;
+                }
+                sacc[kb][r] = p * (pacc[kb][r] - Dq);     // dS^T
+            }
+        bf16x8 db8[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int mm = 0; mm < 2; ++mm)
+                db8[kb][mm] = pack8(sacc[kb][8 * mm + 0], sacc[kb][8 * mm + 1], sacc[kb][8 * mm + 2],
+                                    sacc[kb][8 * mm + 3], sacc[kb][8 * mm + 4], sacc[kb][8 * mm + 5],
+                                    sacc[kb][8 * mm + 6], sacc[kb][8 * mm + 7]);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const int col4 = 32 * db + 16 * c16 + 4 * (j & 3);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm) {
+                    const int row4 = 32 * kb + 16 * mm + 4 * hh + (j >> 2);
+                    const bf16x8 A = cat4(lds_read_tr4(ldsK, row4, col4), lds_read_tr4(ldsK, row4 + 8, col4));
+                    acc[db] = mfma32(A, db8[kb][mm], acc[db]);
+                }
+        }
+    }
+
+    if (valid) {
+        __bf16* op = a.dq + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                bf16x4 x;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc[db][4 * gq + e] * a.scale);
+                *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * gq) = x;
+            }
+    }
 }
+
+// ------------------------------------------------------------------------------------
+// dkdv pass
+// ------------------------------------------------------------------------------------
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void bwd_dkdv_kernel(BwdArgs a) {
+    constexpr int BNK = 32 * NW, NT = 64 * NW, BQ = 64;
+    constexpr int GR = (BQ * 16) / NT;
+    __shared__ __attribute__((aligned(1024))) char lds[2 * TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) float ldsL[BQ];
+    __shared__ __attribute__((aligned(16))) float ldsD[BQ];
+    char* ldsQ = lds;
+    char* ldsG = lds + TILE_BYTES;
+
+    int tile, kvh;
+    if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
+    // key tiles in ascending order: the first prompt tile is seen by every row (most work)
+    int g, s0;
+    {
+        const int ng = a.tab[0];
+        int base = 0;
+        g = -1; s0 = 0;
+        for (int gi = 0; gi < ng; ++gi) {
+            const int nt = (a.tab[TAB_HEADER + TAB_GROUP_WORDS * gi + 2] + BNK - 1) / BNK;
+            if (tile < base + nt) { g = gi; s0 = (tile - base) * BNK; break; }
+            base += nt;
+        }
+    }
+    if (g < 0) return;
+    const GroupDesc gd = load_group(a.tab, g);
+    const int Lp = gd.Lp, Tg = gd.Tg;
+    const int64_t T_total = a.tab[1];
+
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int c = l & 31, hh = l >> 5, j = l & 15, c16 = (l >> 4) & 1;
+
+    // this lane's key (a column of S) and the rows [s, e_s) that may see it
+    const int s = s0 + 32 * w + c;
+    const bool valid = s < Tg;
+    const int e_s = !valid ? 0 : (s < Lp ? Tg : seg_end(gd, s));
+    const int ws0 = s0 + 32 * w;                       // wave's first key
+    const bool wave_valid = ws0 < Tg;
+    const int ws1 = min(ws0 + 31, Tg - 1);             // wave's last valid key
+    // smallest / largest row bound e_s over the wave's keys (prompt keys: Tg; response
+    // keys: the end of their response, non-decreasing in s)
+    const int e_min = !wave_valid ? 0 : (ws1 < Lp ? Tg : seg_end(gd, max(ws0, Lp)));
+    const int e_max = !wave_valid ? 0 : (ws0 < Lp ? Tg : seg_end(gd, ws1));
+
+    // K and V as B operands (column = this lane's key)
+    bf16x8 kreg[8], vreg[8];
+    {
+        const int64_t row = ((int64_t)(gd.tok_base + (valid ? s : 0)) * a.Hkv + kvh) * 128 + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            bf16x8 x = *reinterpret_cast<const bf16x8*>(a.k + row + 16 * ks);
+            bf16x8 y = *reinterpret_cast<const bf16x8*>(a.v + row + 16 * ks);
+            if (!valid) { x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0}; y = x; }
+            kreg[ks] = x; vreg[ks] = y;
+        }
+    }
+
+    // rows that see any key of the workgroup's tile
+    const int s1 = min(s0 + BNK, Tg);
+    const int row_end = s0 < Lp ? Tg : seg_end(gd, s1 - 1);
+    const int qt0 = s0 / BQ, qt1 = (row_end + BQ - 1) / BQ;
+    const int rep = a.Hq / a.Hkv;
+    const int total = (qt1 - qt0) * rep;
+
+    const int64_t q_stride = (int64_t)a.Hq * 128;
+    i32x4 qpre[GR], gpre[GR];
+    float lpre = 0.f, dpre = 0.f;
+    auto load_regs = [&](int it) {
+        const int hr = it / (qt1 - qt0), qt = qt0 + it % (qt1 - qt0);
+        const int head = kvh * rep + hr;
+        const __bf16* qb = a.q + ((int64_t)gd.tok_base * a.Hq + head) * 128;
+        const __bf16* gb = a.d_o + ((int64_t)gd.tok_base * a.Hq + head) * 128;
+#pragma unroll
+        for (int i = 0; i < GR; ++i) {
+            const int gid = tid + NT * i;
+            const int row = gid >> 4, gr = gid & 15;
+            const int t = qt * BQ + row;
+            i32x4 qq = {0, 0, 0, 0}, gg = {0, 0, 0, 0};
+            if (t < Tg) {
+                qq = *reinterpret_cast<const i32x4*>(qb + (int64_t)t * q_stride + gr * 8);
+                gg = *reinterpret_cast<const i32x4*>(gb + (int64_t)t * q_stride + gr * 8);
+            }
+            qpre[i] = qq; gpre[i] = gg;
+        }
+        if (tid < BQ) {
+            const int t = qt * BQ + tid;
+            lpre = 0.f; dpre = 0.f;
+            if (t < Tg) {
+                lpre = a.lse[(int64_t)head * T_total + gd.tok_base + t] * LOG2E;
+                dpre = a.D[(int64_t)head * T_total + gd.tok_base + t];
+            }
+        }
+    };
+    auto store_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < GR; ++i) {
+            const int gid = tid + NT * i;
+            const int row = gid >> 4, gr = gid & 15;
+            *reinterpret_cast<i32x4*>(ldsQ + tile_off(row, gr)) = qpre[i];
+            *reinterpret_cast<i32x4*>(ldsG + tile_off(row, gr)) = gpre[i];
+        }
+        if (tid < BQ) { ldsL[tid] = lpre; ldsD[tid] = dpre; }
+    };
+
+    f32x16 dkacc[4], dvacc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
+    const float cs = a.c;
+
+    if (total > 0) load_regs(0);
+    for (int it = 0; it < total; ++it) {
+        const int qt = qt0 + it % (qt1 - qt0);
+        __syncthreads();
+        store_lds();
+        __syncthreads();
+        if (it + 1 < total) load_regs(it + 1);
+
+        const int r0 = qt * BQ;
+        // no row of this tile sees any key of this wave
+        const bool skip = !wave_valid || r0 + BQ - 1 < ws0 || r0 >= e_max;
+        if (skip) continue;
+
+        f32x16 sacc[2], pacc[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; pacc[qb][r] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 A = lds_read_row8(ldsQ, 32 * qb + c, 2 * ks + hh);
+                sacc[qb] = mfma32(A, kreg[ks], sacc[qb]);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 A = lds_read_row8(ldsG, 32 * qb + c, 2 * ks + hh);
+                pacc[qb] = mfma32(A, vreg[ks], pacc[qb]);
+            }
+        }
+        // every row of the tile sees every key of the wave
+        const bool full = r0 >= ws1 && ws0 + 31 < Tg && r0 + BQ <= e_min;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int rr = 32 * qb + 8 * gq + 4 * hh;
+                const f32x4 L4 = *reinterpret_cast<const f32x4*>(&ldsL[rr]);
+                const f32x4 D4 = *reinterpret_cast<const f32x4*>(&ldsD[rr]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * gq + e;
+                    float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][r], cs, -L4[e]));
+                    if (!full) {
+                        const int t = r0 + rr + e;
+                        p = (t >= s && t < e_s) ? p : 0.f;
+                    }
+                    sacc[qb][r] = p;                              // P
+                    pacc[qb][r] = p * (pacc[qb][r] - D4[e]);      // dS
+                }
+            }
+        bf16x8 p8[2][2], d8[2][2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int mm = 0; mm < 2; ++mm) {
+                p8[qb][mm] = pack8(sacc[qb][8 * mm + 0], sacc[qb][8 * mm + 1], sacc[qb][8 * mm + 2],
+                                   sacc[qb][8 * mm + 3], sacc[qb][8 * mm + 4], sacc[qb][8 * mm + 5],
+                                   sacc[qb][8 * mm + 6], sacc[qb][8 * mm + 7]);
+                d8[qb][mm] = pack8(pacc[qb][8 * mm + 0], pacc[qb][8 * mm + 1], pacc[qb][8 * mm + 2],
+                                   pacc[qb][8 * mm + 3], pacc[qb][8 * mm + 4], pacc[qb][8 * mm + 5],
+                                   pacc[qb][8 * mm + 6], pacc[qb][8 * mm + 7]);
+            }
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const int col4 = 32 * db + 16 * c16 + 4 * (j & 3);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm) {
+                    const int row4 = 32 * qb + 16 * mm + 4 * hh + (j >> 2);
+                    const bf16x8 Ag = cat4(lds_read_tr4(ldsG, row4, col4), lds_read_tr4(ldsG, row4 + 8, col4));
+                    dvacc[db] = mfma32(Ag, p8[qb][mm], dvacc[db]);
+                    const bf16x8 Aq = cat4(lds_read_tr4(ldsQ, row4, col4), lds_read_tr4(ldsQ, row4 + 8, col4));
+                    dkacc[db] = mfma32(Aq, d8[qb][mm], dkacc[db]);
+                }
+        }
+    }
+
+    if (valid) {
+        const int64_t row = ((int64_t)(gd.tok_base + s) * a.Hkv + kvh) * 128 + 4 * hh;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                bf16x4 xk, xv;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    xk[e] = (__bf16)(dkacc[db][4 * gq + e] * a.scale);
+                    xv[e] = (__bf16)(dvacc[db][4 * gq + e]);
+                }
+                *reinterpret_cast<bf16x4*>(a.dk + row + 32 * db + 8 * gq) = xk;
+                *reinterpret_cast<bf16x4*>(a.dv + row + 32 * db + 8 * gq) = xv;
+            }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
+    hipError_t e = launch_rowsum(p, false, s);
+    if (e != hipSuccess) return e;
+    BwdArgs a;
+    a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v; a.d_o = (const __bf16*)p.d_o;
+    a.lse = p.lse; a.D = p.Dbuf;
+    a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;
+    a.tab = p.tab; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
+    constexpr int NW = 4;
+    {
+        a.n_tiles = count_tiles(p, 32 * NW);
+        const int grid = grid_for_items(a.n_tiles, p.Hkv, p.Hkv);
+        hipLaunchKernelGGL(bwd_dkdv_kernel<NW>, dim3(grid), dim3(NW * 64), 0, s, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    {
+        a.n_tiles = count_tiles(p, 32 * NW);
+        const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
+        hipLaunchKernelGGL(bwd_dq_kernel<NW>, dim3(grid), dim3(NW * 64), 0, s, a);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace sp
