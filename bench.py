@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the shared-prompt attention hot path on one MI355X.
+
+A "step" is one forward (O, LSE) plus one backward (D, dK/dV pass, dQ pass) of the
+headline workload: config 5, the largest long-prompt configuration (one group,
+prompt 16384, 32 ragged responses, 40 q / 8 kv heads, head_dim 128, bf16).  Inputs are
+seeded synthetic tensors already resident in HBM.  `value` is useful (mask-counted)
+TFLOP/s over forward+backward; forward-only and backward-only rates, each stage's mean
+duration (HIP events on the launch stream, inside the timed region) and the roofline of
+the dominant kernel are reported beside it, with the CPU oracle timed on a bounded
+sample of the same workload.
+
+usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+
+
+def parse_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel`, taken from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None if absent."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    pat = re.compile(rf"^{re.escape(kernel)}\s+hbm_bytes_per_launch\s+([0-9.eE+]+)")
+    with open(path) as f:
+        for line in f:
+            m = pat.match(line.strip())
+            if m:
+                return float(m.group(1))
+    return None
+
+
+def cpu_baseline(w, t, target_seconds=20.0):
+    """Time the fp64 oracle (as it stands) on one q head of the workload: forward and
+    backward over all rows of that head.  Useful FLOPs covered = 14 * d * pairs."""
+    import numpy as np
+    from oracle import sp_attn_oracle as orc
+    from paper_2511_18871_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    g = w.groups[0]
+    n = g.total
+    sl = slice(0, n)
+    rep = w.n_q_heads // w.n_kv_heads
+    t0 = time.perf_counter()
+    orc.sp_attn_bwd(t.q[sl], t.k[sl], t.v[sl], t.d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale,
+                    kv_heads=[0], q_heads=[0], row_block=1024)
+    dt = time.perf_counter() - t0
+    flops = 14.0 * w.head_dim * W.allowed_pairs(g)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"q head 0 of {w.n_q_heads} (kv head 0), all {n} rows of group 0, forward+backward in "
+                      f"fp64, {dt:.1f} s",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
+    ap.add_argument("--naive", action="store_true", help="also time the naive packed-causal forward")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2511_18871_amd import binding as B
+    from paper_2511_18871_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load_library()
+    w = W.config(args.config)
+    t = W.make_tensors(w)
+    dev = torch.device("cuda:0")
+    q, k, v = t.q.to(dev), t.k.to(dev), t.v.to(dev)
+    d_o = t.d_o.to(dev) if t.d_o is not None else None
+    pl, Gs, rl = w.prompt_lens(), w.Gs(), w.resp_lens_flat()
+    scale = w.softmax_scale
+    T, Hq, Hkv, d = w.total_tokens, w.n_q_heads, w.n_kv_heads, w.head_dim
+    code = B.SP_BF16 if w.dtype == torch.bfloat16 else B.SP_F32
+    o = torch.empty_like(q)
+    lse = torch.empty(Hq, T, dtype=torch.float32, device=dev)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, Hkv, d, code), dtype=torch.uint8, device=dev)
+    do_bwd = w.backward
+
+    stage_names = ["fwd"] + (["bwd_rowsum", "bwd_dkdv", "bwd_dq"] if do_bwd else [])
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, scale, o=o, lse=lse, workspace=ws)
+        mark(1)
+        if do_bwd:
+            B.sp_attn_bwd_batched_stages(q, k, v, o, lse, d_o, pl, Gs, rl, scale, B.SP_BWD_STAGE_ROWSUM, ws)
+            mark(2)
+            B.sp_attn_bwd_batched_stages(q, k, v, None, lse, d_o, pl, Gs, rl, scale, B.SP_BWD_STAGE_DKDV, ws,
+                                         dk=dk, dv=dv)
+            mark(3)
+            B.sp_attn_bwd_batched_stages(q, k, v, None, lse, d_o, pl, Gs, rl, scale, B.SP_BWD_STAGE_DQ, ws, dq=dq)
+            mark(4)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    n_ev = len(stage_names) + 1
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    stage_ms = {}
+    for si, name in enumerate(stage_names):
+        stage_ms[name] = sum(evs[i][si].elapsed_time(evs[i][si + 1]) for i in range(args.steps)) / args.steps
+
+    fwd_flops = W.useful_flops(w, False) / w.n_sets
+    bwd_flops = W.useful_flops(w, True) / w.n_sets if do_bwd else 0.0
+    total_flops = fwd_flops + bwd_flops
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+    fwd_tf = fwd_flops / (stage_ms["fwd"] * 1e-3) / 1e12
+
+    out = {
+        "metric": "shared-prompt attn fwd+bwd useful TFLOP/s and % bf16 MFMA peak, 1xMI355X",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "groups": len(w.groups), "prompt_len": w.groups[0].prompt_len,
+                   "G": len(w.groups[0].resp_lens), "total_tokens": T, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "head_dim": d, "passes": "fwd+bwd" if do_bwd else "fwd"},
+        "pct_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "fwd": {"ms": round(stage_ms["fwd"], 4), "tflops": round(fwd_tf, 2),
+                "pct_peak": round(100.0 * fwd_tf / PEAK_BF16_TFLOPS, 2)},
+        "stage_ms": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
+    }
+    if do_bwd:
+        bwd_ms = stage_ms["bwd_rowsum"] + stage_ms["bwd_dkdv"] + stage_ms["bwd_dq"]
+        bwd_tf = bwd_flops / (bwd_ms * 1e-3) / 1e12
+        out["bwd"] = {"ms": round(bwd_ms, 4), "tflops": round(bwd_tf, 2),
+                      "pct_peak": round(100.0 * bwd_tf / PEAK_BF16_TFLOPS, 2)}
+        # dominant kernel: the dkdv pass.  Algorithmic FLOPs per launch: its four contractions
+        # (S, dP, dV, dK) are all required for dK/dV = 8*d per allowed pair per q head.
+        dk_flops = 0.8 * bwd_flops
+        ach = dk_flops / (stage_ms["bwd_dkdv"] * 1e-3) / 1e12
+        out["roofline"] = {"kernel": "bwd_dkdv_kernel", "bound": "mfma", "achieved": round(ach, 2),
+                           "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                           "traffic": parse_traffic(w.name, "bwd_dkdv_kernel")}
+    else:
+        out["roofline"] = {"kernel": "fwd_kernel", "bound": "mfma", "achieved": round(fwd_tf, 2),
+                           "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(fwd_tf / PEAK_BF16_TFLOPS, 4),
+                           "traffic": parse_traffic(w.name, "fwd_kernel")}
+    out["roofline_fwd"] = {"kernel": "fwd_kernel", "bound": "mfma", "achieved": round(fwd_tf, 2),
+                           "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(fwd_tf / PEAK_BF16_TFLOPS, 4),
+                           "traffic": parse_traffic(w.name, "fwd_kernel")}
+
+    if args.naive:
+        evn = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, scale, schedule=B.SP_SCHED_NAIVE_CAUSAL, o=o, lse=lse, workspace=ws)
+        evn[0].record()
+        for _ in range(5):
+            B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, scale, schedule=B.SP_SCHED_NAIVE_CAUSAL, o=o, lse=lse,
+                                  workspace=ws)
+        evn[1].record()
+        torch.cuda.synchronize()
+        nms = evn[0].elapsed_time(evn[1]) / 5
+        out["naive_fwd"] = {"ms": round(nms, 4), "useful_tflops": round(fwd_flops / (nms * 1e-3) / 1e12, 2)}
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = {k_: (round(v_, 6) if isinstance(v_, float) else v_)
+                               for k_, v_ in cpu_baseline(w, t).items()}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

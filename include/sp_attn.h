@@ -118,6 +118,27 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v,
                               float softmax_scale, sp_dtype dtype,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* The backward runs in three stages that a caller may enqueue separately, e.g. to time
+ * them or to overlap the two gradient passes on two streams:
+ *   SP_BWD_STAGE_ROWSUM  D[h, t] = sum_j d_o[t,h,j] * o[t,h,j]  -> workspace (needs o, d_o)
+ *   SP_BWD_STAGE_DKDV    dk, dv  (needs D in the same workspace; o unused)
+ *   SP_BWD_STAGE_DQ      dq      (needs D in the same workspace; o unused)
+ * DKDV and DQ are independent of each other; both must be ordered after ROWSUM on the
+ * same workspace.  Output pointers of stages that are not requested may be NULL.
+ * sp_attn_bwd_batched(...) is this call with SP_BWD_STAGE_ALL. */
+#define SP_BWD_STAGE_ROWSUM 1u
+#define SP_BWD_STAGE_DKDV   2u
+#define SP_BWD_STAGE_DQ     4u
+#define SP_BWD_STAGE_ALL    7u
+sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v,
+                                     const void* o, const float* lse, const void* d_o,
+                                     void* dq, void* dk, void* dv,
+                                     int32_t n_groups, const int32_t* prompt_lens,
+                                     const int32_t* Gs, const int32_t* resp_lens_flat,
+                                     int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                     float softmax_scale, sp_dtype dtype, uint32_t stages,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* Text of the most recent error on the calling thread ("" if none).  The pointer
  * refers to thread-local static storage; the caller must not free it. */
 const char* sp_attn_last_error(void);

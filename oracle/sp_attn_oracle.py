@@ -121,12 +121,14 @@ def sp_attn_fwd(q, k, v, prompt_len: int, resp_lens: Sequence[int], scale: float
 
 
 def sp_attn_bwd(q, k, v, d_o, prompt_len: int, resp_lens: Sequence[int], scale: float,
-                kv_heads: Optional[Sequence[int]] = None, row_block: Optional[int] = None):
+                kv_heads: Optional[Sequence[int]] = None, row_block: Optional[int] = None,
+                q_heads: Optional[Sequence[int]] = None):
     """Backward for one group, recomputing the forward in float64.
 
     d_o: [T, Hq, d].  Returns (dQ [T, Hq, d], dK [T, Hkv, d], dV [T, Hkv, d],
     O [T, Hq, d], LSE [Hq, T]).  With ``kv_heads`` given, only those kv heads
-    and the q heads that read them are computed; the rest stay zero.
+    and the q heads that read them are computed; the rest stay zero.  With ``q_heads``
+    given, only those q heads contribute (dK/dV are then partial sums over them).
     """
     q, k, v, d_o = _as64(q), _as64(k), _as64(v), _as64(d_o)
     T, Hq, d = q.shape
@@ -140,6 +142,8 @@ def sp_attn_bwd(q, k, v, d_o, prompt_len: int, resp_lens: Sequence[int], scale: 
     all_rows = np.arange(T)
     for g in kv_heads:
         for h in range(g * rep, (g + 1) * rep):
+            if q_heads is not None and h not in q_heads:
+                continue
             for rb in _row_blocks(all_rows, row_block):
                 P, lse = _softmax_rows(scale * (q[rb, h, :] @ k[:, g, :].T), M[rb])
                 o = P @ v[:, g, :]

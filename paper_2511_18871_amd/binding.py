@@ -18,8 +18,10 @@ SP_ERR_INVALID_ARG, SP_ERR_UNSUPPORTED, SP_ERR_WORKSPACE, SP_ERR_DEVICE = 1, 2, 
 SP_BF16, SP_F32 = 0, 1
 SP_SCHED_SHARED, SP_SCHED_NAIVE_CAUSAL = 0, 1
 
+SP_BWD_STAGE_ROWSUM, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2, 4, 7
+
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
-           "sp_attn_bwd_batched", "sp_attn_last_error", "sp_attn_version")
+           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_last_error", "sp_attn_version")
 
 _lib = None
 
@@ -54,6 +56,9 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_bwd_batched.restype = ctypes.c_int
     lib.sp_attn_bwd_batched.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32,
                                         ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_bwd_batched_stages.restype = ctypes.c_int
+    lib.sp_attn_bwd_batched_stages.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32,
+                                               f32, ctypes.c_int, ctypes.c_uint32, vp, sz, vp]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
     lib.sp_attn_last_error.argtypes = []
     lib.sp_attn_version.restype = ctypes.c_char_p
@@ -162,3 +167,19 @@ def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Se
                                    _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
                                    _dtype_code(q), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def sp_attn_bwd_batched_stages(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],
+                               resp_lens_flat: Sequence[int], softmax_scale: float, stages: int, workspace,
+                               dq=None, dk=None, dv=None, stream=None) -> None:
+    """Enqueue a subset of the backward stages (SP_BWD_STAGE_* bits).  The caller passes the
+    workspace, because D written by the ROWSUM stage is read by the other two."""
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    ptr = lambda x: None if x is None else x.data_ptr()
+    _check(lib.sp_attn_bwd_batched_stages(q.data_ptr(), k.data_ptr(), v.data_ptr(), ptr(o), lse.data_ptr(),
+                                          d_o.data_ptr(), ptr(dq), ptr(dk), ptr(dv), len(prompt_lens),
+                                          _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d,
+                                          softmax_scale, _dtype_code(q), stages, workspace.data_ptr(),
+                                          workspace.numel(), _stream_ptr(stream)))

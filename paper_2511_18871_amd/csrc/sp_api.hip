@@ -95,12 +95,14 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
               const void* d_o, void* o_out, float* lse_out, void* dq, void* dk, void* dv,
               int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
               int32_t Hq, int32_t Hkv, int32_t d, float scale, sp_dtype dtype, sp_schedule schedule,
-              void* workspace, size_t workspace_bytes, void* stream) {
+              unsigned stages, void* workspace, size_t workspace_bytes, void* stream) {
     g_err[0] = 0;
     sp_status st = check_geometry(Hq, Hkv, d, scale, dtype);
     if (st != SP_OK) return st;
     if (schedule != SP_SCHED_SHARED && schedule != SP_SCHED_NAIVE_CAUSAL)
         return fail(SP_ERR_INVALID_ARG, "unknown schedule %d", (int)schedule);
+    if (bwd && (stages == 0 || (stages & ~(unsigned)SP_BWD_STAGE_ALL)))
+        return fail(SP_ERR_INVALID_ARG, "stages=0x%x is not a non-empty subset of SP_BWD_STAGE_ALL", stages);
     const void* ptrs[] = {q, k, v, bwd ? o : o_out, bwd ? (const void*)lse : (const void*)lse_out,
                           bwd ? d_o : q, bwd ? dq : q, bwd ? dk : q, bwd ? dv : q};
     for (const void* p : ptrs) {
@@ -124,6 +126,7 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
     p.Hq = Hq; p.Hkv = Hkv; p.head_dim = d; p.scale = scale;
     p.naive = schedule == SP_SCHED_NAIVE_CAUSAL;
+    p.stages = stages;
     p.host_group_tokens = L.group_tokens.data();
 
     hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
@@ -153,7 +156,7 @@ sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, floa
                       int32_t head_dim, float softmax_scale, sp_dtype dtype, void* workspace,
                       size_t workspace_bytes, void* stream) {
     return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, 1, &prompt_len, &G,
-               resp_lens, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, workspace,
+               resp_lens, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, workspace,
                workspace_bytes, stream);
 }
 
@@ -162,7 +165,7 @@ sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o
                       int32_t G, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
                       sp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
     return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, 1, &prompt_len, &G, resp_lens, n_q_heads,
-               n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, workspace, workspace_bytes, stream);
+               n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, workspace, workspace_bytes, stream);
 }
 
 sp_status sp_attn_fwd_batched(const void* q, const void* k, const void* v, void* o, float* lse, int32_t n_groups,
@@ -171,7 +174,7 @@ sp_status sp_attn_fwd_batched(const void* q, const void* k, const void* v, void*
                               sp_dtype dtype, sp_schedule schedule, void* workspace, size_t workspace_bytes,
                               void* stream) {
     return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, n_groups, prompt_lens,
-               Gs, resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, schedule, workspace,
+               Gs, resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, schedule, SP_BWD_STAGE_ALL, workspace,
                workspace_bytes, stream);
 }
 
@@ -181,8 +184,23 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v, const
                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
                               sp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
     return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs, resp_lens_flat,
-               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, workspace, workspace_bytes,
+               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, workspace, workspace_bytes,
                stream);
+}
+
+sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                     const void* d_o, void* dq, void* dk, void* dv, int32_t n_groups,
+                                     const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                                     int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                                     sp_dtype dtype, uint32_t stages, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+    // outputs of stages that do not run may be NULL: substitute q so the pointer checks pass
+    if (!(stages & SP_BWD_STAGE_ROWSUM) && !o) o = q;
+    if (!(stages & SP_BWD_STAGE_DQ) && !dq) dq = const_cast<void*>(q);
+    if (!(stages & SP_BWD_STAGE_DKDV)) { if (!dk) dk = const_cast<void*>(q); if (!dv) dv = const_cast<void*>(q); }
+    return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs, resp_lens_flat,
+               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, stages, workspace,
+               workspace_bytes, stream);
 }
 
 const char* sp_attn_last_error(void) { return g_err; }

@@ -418,22 +418,25 @@ __global__ __launch_bounds__(NW * 64) void bwd_dkdv_kernel(BwdArgs a) {
 }  // namespace
 
 hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
-    hipError_t e = launch_rowsum(p, false, s);
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (p.stages & STAGE_ROWSUM) {
+        e = launch_rowsum(p, false, s);
+        if (e != hipSuccess) return e;
+    }
     BwdArgs a;
     a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v; a.d_o = (const __bf16*)p.d_o;
     a.lse = p.lse; a.D = p.Dbuf;
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;
     a.tab = p.tab; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
     constexpr int NW = 4;
-    {
+    if (p.stages & STAGE_DKDV) {
         a.n_tiles = count_tiles(p, 32 * NW);
         const int grid = grid_for_items(a.n_tiles, p.Hkv, p.Hkv);
         hipLaunchKernelGGL(bwd_dkdv_kernel<NW>, dim3(grid), dim3(NW * 64), 0, s, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    {
+    if (p.stages & STAGE_DQ) {
         a.n_tiles = count_tiles(p, 32 * NW);
         const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
         hipLaunchKernelGGL(bwd_dq_kernel<NW>, dim3(grid), dim3(NW * 64), 0, s, a);

@@ -251,14 +251,18 @@ hipError_t launch_fwd_f32(const Problem& p, hipStream_t s) {
 }
 
 hipError_t launch_bwd_f32(const Problem& p, hipStream_t s) {
-    hipError_t e = launch_rowsum(p, true, s);
-    if (e != hipSuccess) return e;
+    if (p.stages & STAGE_ROWSUM) {
+        hipError_t e = launch_rowsum(p, true, s);
+        if (e != hipSuccess) return e;
+    }
     const int gq = blocks_for_waves(p.total_tokens * p.Hq);
     const int gk = blocks_for_waves(p.total_tokens * p.Hkv);
 #define SP_F32_BWD(DH)                                                                                      \
+    if (p.stages & STAGE_DQ)                                                                               \
     hipLaunchKernelGGL(bwd_dq_f32_kernel<DH>, dim3(gq), dim3(256), 0, s, (const float*)p.q, (const float*)p.k, \
                        (const float*)p.v, (const float*)p.d_o, p.lse, p.Dbuf, (float*)p.dq, p.tab, p.Hq,   \
                        p.Hkv, p.scale);                                                                    \
+    if (p.stages & STAGE_DKDV)                                                                             \
     hipLaunchKernelGGL(bwd_dkdv_f32_kernel<DH>, dim3(gk), dim3(256), 0, s, (const float*)p.q,              \
                        (const float*)p.k, (const float*)p.v, (const float*)p.d_o, p.lse, p.Dbuf,           \
                        (float*)p.dk, (float*)p.dv, p.tab, p.Hq, p.Hkv, p.scale);

@@ -5,6 +5,8 @@
 
 namespace sp {
 
+constexpr unsigned STAGE_ROWSUM = 1u, STAGE_DKDV = 2u, STAGE_DQ = 4u;
+
 struct Problem {
     const void* q; const void* k; const void* v;
     const void* o; const float* lse; const void* d_o;     // backward inputs (o also fwd output)
@@ -18,6 +20,7 @@ struct Problem {
     int Hq, Hkv, head_dim;
     float scale;
     int naive;                                            // forward: naive packed-causal schedule
+    unsigned stages;                                      // backward: SP_BWD_STAGE_* bits to run
     // host copies of the per-group token counts, for grid sizing
     const int* host_group_tokens;
 };

@@ -1,0 +1,74 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_18871_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load_library()
+
+
+def declared_symbols():
+    with open(os.path.join(ROOT, "include", "sp_attn.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(sp_attn_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(raw, n) is not None
+
+
+def test_version_and_workspace_size(lib):
+    assert lib.sp_attn_version().decode() == "0.1"
+    fwd = B.workspace_bytes(False, 1000, 2, 7, 8, 2, 128, B.SP_BF16)
+    bwd = B.workspace_bytes(True, 1000, 2, 7, 8, 2, 128, B.SP_BF16)
+    assert fwd >= (4 + 6 * 2 + 7 + 2) * 4 and fwd % 256 == 0
+    assert bwd - fwd >= 8 * 1000 * 4
+    assert B.workspace_bytes(False, 0, 1, 0, 8, 2, 128, B.SP_BF16) == 0
+
+
+def _call_fwd(lib, *, q=0x1000, k=0x1000, v=0x1000, o=0x1000, lse=0x1000, lp=4, lens=(3,), Hq=4, Hkv=2, d=128,
+              scale=0.1, dtype=B.SP_BF16, ws=0x1000, ws_bytes=1 << 20):
+    arr = (ctypes.c_int32 * max(1, len(lens)))(*lens)
+    return lib.sp_attn_fwd(q, k, v, o, lse, lp, arr, len(lens), Hq, Hkv, d, scale, dtype, ws, ws_bytes, None)
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    """Every call below must fail validation, so no kernel is launched and the fake
+    device addresses are never dereferenced."""
+    assert _call_fwd(lib, q=None) == B.SP_ERR_INVALID_ARG
+    assert _call_fwd(lib, q=0x1004) == B.SP_ERR_INVALID_ARG
+    assert _call_fwd(lib, lp=-1) == B.SP_ERR_INVALID_ARG
+    assert _call_fwd(lib, lens=(3, -2)) == B.SP_ERR_INVALID_ARG
+    assert _call_fwd(lib, lp=0, lens=(0, 0)) == B.SP_ERR_INVALID_ARG      # empty group
+    assert _call_fwd(lib, Hq=5, Hkv=2) == B.SP_ERR_INVALID_ARG
+    assert _call_fwd(lib, scale=0.0) == B.SP_ERR_INVALID_ARG
+    assert _call_fwd(lib, scale=float("nan")) == B.SP_ERR_INVALID_ARG
+    assert _call_fwd(lib, d=96) == B.SP_ERR_UNSUPPORTED
+    assert _call_fwd(lib, d=64) == B.SP_ERR_UNSUPPORTED                   # bf16 needs 128
+    assert _call_fwd(lib, dtype=7) == B.SP_ERR_UNSUPPORTED
+    assert _call_fwd(lib, ws=None) == B.SP_ERR_WORKSPACE
+    assert _call_fwd(lib, ws_bytes=16) == B.SP_ERR_WORKSPACE
+    assert b"workspace" in lib.sp_attn_last_error()
+
+
+def test_bad_stage_mask_is_rejected(lib):
+    one = (ctypes.c_int32 * 1)(4)
+    g = (ctypes.c_int32 * 1)(1)
+    r = (ctypes.c_int32 * 1)(3)
+    for stages in (0, 8, 15):
+        st = lib.sp_attn_bwd_batched_stages(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000,
+                                            1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, stages, 0x1000, 1 << 20, None)
+        assert st == B.SP_ERR_INVALID_ARG
