@@ -179,6 +179,26 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
 
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
 
+// max / sum of x over the lane pair (l, l ^ 32) with one v_permlane32_swap: after the swap
+// one result holds the low-half value and the other the high-half value in every lane.
+__device__ __forceinline__ float pair_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Asynchronous global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane i of
+// the wave writes LDS bytes [lds_base + 16*i, +16).  lds_base must be wave-uniform.
+__device__ __forceinline__ void async_copy16(const void* gptr, char* lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+// wait until every global load (including global -> LDS copies) of this wave has landed
+__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 

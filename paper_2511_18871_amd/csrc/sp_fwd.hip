@@ -33,11 +33,9 @@ struct FwdArgs {
 
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void fwd_kernel(FwdArgs a) {
-    constexpr int BM = 32 * NW, NT = 64 * NW;
-    constexpr int GR = (BN * 16) / NT;          // 16-byte granules per thread per tile
-    __shared__ __attribute__((aligned(1024))) char lds[2 * TILE_BYTES];
-    char* ldsK = lds;
-    char* ldsV = lds + TILE_BYTES;
+    constexpr int BM = 32 * NW;
+    constexpr int CH = 32 / NW;                 // 1 KB chunks (4 tile rows) each wave copies per tile
+    __shared__ __attribute__((aligned(1024))) char lds[2][2 * TILE_BYTES];   // [buffer][K | V]
 
     int tile, head;
     if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
@@ -96,28 +94,19 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(FwdArgs a) {
     const __bf16* kbase = a.k + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
     const __bf16* vbase = a.v + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
 
-    i32x4 kpre[GR], vpre[GR];
-    auto load_regs = [&](int kt) {
+    // Asynchronous tile copy, global -> LDS.  Chunk ci (0..15 K, 16..31 V) is 4 tile rows;
+    // lane i fills granule slot (i & 15) of row 4*(ci & 15) + (i >> 4), so it fetches the
+    // granule that the swizzle maps to that slot.  Rows past the end of the group re-read the
+    // group's last row: those keys are always masked, the values only have to be finite.
+    auto issue_tile = [&](int kt, int buf) {
 #pragma unroll
-        for (int i = 0; i < GR; ++i) {
-            const int gid = tid + NT * i;
-            const int row = gid >> 4, gr = gid & 15;
-            const int s = kt * BN + row;
-            i32x4 kk = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (s < Tg) {
-                kk = *reinterpret_cast<const i32x4*>(kbase + (int64_t)s * kv_stride + gr * 8);
-                vv = *reinterpret_cast<const i32x4*>(vbase + (int64_t)s * kv_stride + gr * 8);
-            }
-            kpre[i] = kk; vpre[i] = vv;
-        }
-    };
-    auto store_lds = [&]() {
-#pragma unroll
-        for (int i = 0; i < GR; ++i) {
-            const int gid = tid + NT * i;
-            const int row = gid >> 4, gr = gid & 15;
-            *reinterpret_cast<i32x4*>(ldsK + tile_off(row, gr)) = kpre[i];
-            *reinterpret_cast<i32x4*>(ldsV + tile_off(row, gr)) = vpre[i];
+        for (int u = 0; u < CH; ++u) {
+            const int ci = w * CH + u;
+            const int row = 4 * (ci & 15) + (l >> 4);
+            const int gran = (l & 15) ^ swz(row);
+            const int s = min(kt * BN + row, Tg - 1);
+            const __bf16* src = (ci < 16 ? kbase : vbase) + (int64_t)s * kv_stride + gran * 8;
+            async_copy16(src, &lds[buf][(ci >> 4) * TILE_BYTES + (ci & 15) * 1024]);
         }
     };
     auto tile_at = [&](int it) { return it < n1 ? it : k2b + (it - n1); };
@@ -130,13 +119,15 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(FwdArgs a) {
     float m = -INFINITY, lsum = 0.f;
     const float cs = a.c;
 
-    if (total > 0) load_regs(tile_at(0));
+    if (total > 0) issue_tile(tile_at(0), 0);
     for (int it = 0; it < total; ++it) {
         const int kt = tile_at(it);
-        __syncthreads();
-        store_lds();
-        __syncthreads();
-        if (it + 1 < total) load_regs(tile_at(it + 1));
+        const int buf = it & 1;
+        wait_vm0();            // this wave's share of tile `it` has landed
+        __syncthreads();       // everyone's has; everyone is done reading the other buffer
+        if (it + 1 < total) issue_tile(tile_at(it + 1), buf ^ 1);
+        const char* ldsK = lds[buf];
+        const char* ldsV = lds[buf] + TILE_BYTES;
 
         const int s0 = kt * BN;
         const bool skip = !wave_valid || s0 > tw1 ||
@@ -170,11 +161,19 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(FwdArgs a) {
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
-        mx = fmaxf(mx, xor32(mx));
+        mx = pair_max(mx);
         const float mnew = fmaxf(m, mx);
-        const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-        const float alpha = __builtin_amdgcn_exp2f((m - muse) * cs);
-        const float mc = muse * cs;
+        if (__builtin_amdgcn_ballot_w64(mnew > m) != 0) {      // some row's running max grew
+            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            const float alpha = __builtin_amdgcn_exp2f((m - muse) * cs);
+            lsum *= alpha;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            m = mnew;
+        }
+        const float mc = ((m == -INFINITY) ? 0.f : m) * cs;
         float rowsum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -184,12 +183,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(FwdArgs a) {
                 sacc[kb][r] = p;
                 rowsum += p;
             }
-        lsum = lsum * alpha + rowsum;
-        m = mnew;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        lsum += rowsum;
 
         bf16x8 pb[2][2];
 #pragma unroll
@@ -215,7 +209,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(FwdArgs a) {
     }
 
     // epilogue: O = acc / l, LSE = (m*c + log2 l) * ln 2
-    const float ltot = lsum + xor32(lsum);
+    const float ltot = pair_sum(lsum);
     if (valid) {
         const float inv = 1.0f / ltot;
         __bf16* op = a.o + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
@@ -240,7 +234,7 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
     a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v;
     a.o = (__bf16*)p.o_out; a.lse = p.lse_out; a.tab = p.tab;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive;
-    constexpr int NW = 4;
+    constexpr int NW = 8;
     a.n_tiles = count_tiles(p, 32 * NW);
     const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
     hipLaunchKernelGGL(fwd_kernel<NW>, dim3(grid), dim3(NW * 64), 0, s, a);
