@@ -120,7 +120,8 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v,
 
 /* The backward runs in three stages that a caller may enqueue separately, e.g. to time
  * them or to overlap the two gradient passes on two streams:
- *   SP_BWD_STAGE_ROWSUM  D[h, t] = sum_j d_o[t,h,j] * o[t,h,j]  -> workspace (needs o, d_o)
+ *   SP_BWD_STAGE_ROWSUM  D[h, t] = sum_j d_o[t,h,j] * o[t,h,j] and lse * log2(e) -> workspace
+ *                        (needs o, d_o, lse)
  *   SP_BWD_STAGE_DKDV    dk, dv  (needs D in the same workspace; o unused)
  *   SP_BWD_STAGE_DQ      dq      (needs D in the same workspace; o unused)
  * DKDV and DQ are independent of each other; both must be ordered after ROWSUM on the

@@ -147,7 +147,7 @@ size_t sp_attn_workspace_bytes(int is_bwd, int64_t total_tokens, int32_t n_group
     (void)n_kv_heads; (void)head_dim; (void)dtype;
     if (total_tokens < 1 || n_groups < 1 || total_responses < 0 || n_q_heads < 1) return 0;
     size_t bytes = align256(table_words(n_groups, total_responses) * 4);
-    if (is_bwd) bytes += align256((size_t)n_q_heads * (size_t)total_tokens * 4);
+    if (is_bwd) bytes += align256((size_t)n_q_heads * (size_t)total_tokens * 8);   // D and scaled LSE
     return bytes;
 }
 

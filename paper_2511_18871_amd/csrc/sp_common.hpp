@@ -168,6 +168,26 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Accumulating MFMA whose accumulator is pinned to the accumulation register file (AGPRs).
+// Kernels that run one wave per SIMD use this for long-lived accumulators that only MFMAs
+// touch, which keeps the compiler from shuttling them through VGPRs.  Back-to-back MFMAs on
+// the same accumulator need no wait states; before the accumulator is read by anything else
+// the caller must let the last MFMA drain (mfma_drain()).
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// VGPR-accumulator MFMAs written as assembly, for kernels that mix them with AGPR-pinned
+// accumulators (the compiler would otherwise route every MFMA result through AGPRs and copy
+// it back for the vector ALU).  The hardware does not interlock a vector-ALU read of a
+// fresh MFMA result: call mfma_drain() between the last of these and the first such read.
+__device__ __forceinline__ void mfma32_v0(f32x16& acc, bf16x8 a, bf16x8 b) {    // acc = a * b
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_v(f32x16& acc, bf16x8 a, bf16x8 b) {     // acc += a * b
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 // Round 8 floats to bf16 (round-to-nearest-even, hardware v_cvt_pk_bf16_f32).
 __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
                                         float a4, float a5, float a6, float a7) {
@@ -192,9 +212,23 @@ __device__ __forceinline__ float pair_sum(float x) {
 
 // Asynchronous global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane i of
 // the wave writes LDS bytes [lds_base + 16*i, +16).  lds_base must be wave-uniform.
+// Written as inline assembly so that the compiler does not place a conservative
+// "wait for all global loads" in front of every later LDS read; the kernels order the
+// copy against its readers themselves with wait_vm0() followed by a workgroup barrier.
+// M0 (the LDS base of the copy) is overwritten; gfx9 LDS instructions do not read M0 and
+// nothing else in these kernels keeps a value in it.
 __device__ __forceinline__ void async_copy16(const void* gptr, char* lds_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
-                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+    const unsigned lds_addr = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_addr) : "memory");
+}
+// 4-byte variant: lane i writes LDS bytes [lds_base + 4*i, +4).
+__device__ __forceinline__ void async_copy4(const void* gptr, char* lds_base) {
+    const unsigned lds_addr = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(gptr), "s"(lds_addr) : "memory");
 }
 // wait until every global load (including global -> LDS copies) of this wave has landed
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }

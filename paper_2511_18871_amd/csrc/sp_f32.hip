@@ -35,7 +35,8 @@ __global__ void upload_table_kernel(TabChunk chunk, int* __restrict__ dst, int o
 
 template <typename T>
 __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, const T* __restrict__ o,
-                                                     float* __restrict__ D, int64_t T_total, int Hq, int dh) {
+                                                     const float* __restrict__ lse, float* __restrict__ D,
+                                                     int64_t T_total, int Hq, int dh) {
     const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int l = threadIdx.x & 63;
     if (gw >= T_total * Hq) return;
@@ -46,7 +47,11 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, 
     float acc = 0.f;
     for (int i = l; i < dh; i += 64) acc += (float)a[i] * (float)b[i];
     acc = wave_sum(acc);
-    if (l == 0) D[(int64_t)h * T_total + tok] = acc;
+    if (l == 0) {
+        D[(int64_t)h * T_total + tok] = acc;
+        // second plane: the row's logsumexp in base-2 units, as the MFMA backward consumes it
+        D[(int64_t)Hq * T_total + (int64_t)h * T_total + tok] = lse[(int64_t)h * T_total + tok] * LOG2E;
+    }
 }
 
 template <int DH>
@@ -232,10 +237,10 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
     const int grid = blocks_for_waves(p.total_tokens * p.Hq);
     if (f32)
         hipLaunchKernelGGL(rowsum_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)p.d_o,
-                           (const float*)p.o, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
+                           (const float*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
     else
         hipLaunchKernelGGL(rowsum_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)p.d_o,
-                           (const __bf16*)p.o, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
+                           (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
     return hipGetLastError();
 }
 
