@@ -105,7 +105,7 @@ def main():
     ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, Hkv, d, code), dtype=torch.uint8, device=dev)
     do_bwd = w.backward
 
-    stage_names = ["fwd"] + (["bwd_rowsum", "bwd_dkdv", "bwd_dq"] if do_bwd else [])
+    stage_names = ["fwd"] + (["bwd_rowsum", "bwd_dq", "bwd_dkdv"] if do_bwd else [])
 
     def step(events=None):
         def mark(i):
@@ -117,10 +117,10 @@ def main():
         if do_bwd:
             B.sp_attn_bwd_batched_stages(q, k, v, o, lse, d_o, pl, Gs, rl, scale, B.SP_BWD_STAGE_ROWSUM, ws)
             mark(2)
+            B.sp_attn_bwd_batched_stages(q, k, v, None, lse, d_o, pl, Gs, rl, scale, B.SP_BWD_STAGE_DQ, ws, dq=dq)
+            mark(3)
             B.sp_attn_bwd_batched_stages(q, k, v, None, lse, d_o, pl, Gs, rl, scale, B.SP_BWD_STAGE_DKDV, ws,
                                          dk=dk, dv=dv)
-            mark(3)
-            B.sp_attn_bwd_batched_stages(q, k, v, None, lse, d_o, pl, Gs, rl, scale, B.SP_BWD_STAGE_DQ, ws, dq=dq)
             mark(4)
 
     for _ in range(args.warmup):

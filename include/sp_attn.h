@@ -122,10 +122,14 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v,
  * them or to overlap the two gradient passes on two streams:
  *   SP_BWD_STAGE_ROWSUM  D[h, t] = sum_j d_o[t,h,j] * o[t,h,j] and lse * log2(e) -> workspace
  *                        (needs o, d_o, lse)
+ *   SP_BWD_STAGE_DQ      dq      (needs D in the same workspace; o unused).  On the bf16 path it
+ *                        also replaces D in the workspace by sum_s P*dP, the same quantity
+ *                        evaluated in fp32 without the bf16 rounding of o.
  *   SP_BWD_STAGE_DKDV    dk, dv  (needs D in the same workspace; o unused)
- *   SP_BWD_STAGE_DQ      dq      (needs D in the same workspace; o unused)
- * DKDV and DQ are independent of each other; both must be ordered after ROWSUM on the
- * same workspace.  Output pointers of stages that are not requested may be NULL.
+ * Both gradient stages must be ordered after ROWSUM on the same workspace.  They may run in
+ * either order, but DKDV is more accurate (and the pair is bitwise repeatable) when it is
+ * ordered after DQ, which is what sp_attn_bwd* do.  Output pointers of stages that are not
+ * requested may be NULL.
  * sp_attn_bwd_batched(...) is this call with SP_BWD_STAGE_ALL. */
 #define SP_BWD_STAGE_ROWSUM 1u
 #define SP_BWD_STAGE_DKDV   2u

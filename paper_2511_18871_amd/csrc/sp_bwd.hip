@@ -24,7 +24,7 @@ constexpr int TILE_BYTES = 64 * 256;   // 64 rows x 128 bf16
 
 struct BwdArgs {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* d_o;
-    const float* lse; const float* D; const float* L2;   // L2 = lse * log2(e), written by the rowsum stage
+    const float* lse; float* D; const float* L2;   // L2 = lse * log2(e), written by the rowsum stage
     __bf16* dq; __bf16* dk; __bf16* dv;
     const int* tab;
     int n_tiles, Hq, Hkv;
@@ -114,6 +114,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     const float cs = a.c;
+    float dsum = 0.f;      // sum over this lane's keys of P * dP: an O-free, fp32 evaluation of D
 
     if (total > 0) issue_tile(tile_at(0), 0);
     for (int it = 0; it < total; ++it) {
@@ -156,6 +157,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
                     const bool ok = key <= tm && (key < Lp || key >= st);
                     p = ok ? p : 0.f;
                 }
+                dsum = __builtin_fmaf(p, pacc[kb][r], dsum);
                 sacc[kb][r] = p * (pacc[kb][r] - Dq);     // dS^T
             }
         bf16x8 db8[2][2];
@@ -180,6 +182,10 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
         }
     }
 
+    // D = sum_s P dP equals rowsum(dO * O) exactly, but does not inherit the bf16 rounding of O.
+    // Publish it for the dkdv pass (this workgroup owns these rows of D, so overwriting is safe).
+    dsum = pair_sum(dsum);
+    if (valid && hh == 0) a.D[(int64_t)head * T_total + gd.tok_base + t] = dsum;
     if (valid) {
         __bf16* op = a.dq + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
 #pragma unroll
@@ -423,18 +429,18 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;
     a.tab = p.tab; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
     constexpr int NW = 4;
-    if (p.stages & STAGE_DKDV) {
-        a.n_tiles = count_tiles(p, 128);
-        const int grid = grid_for_items(a.n_tiles, p.Hkv, p.Hkv);
-        hipLaunchKernelGGL(bwd_dkdv_kernel, dim3(grid), dim3(512), 0, s, a);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
     if (p.stages & STAGE_DQ) {
         constexpr int NWQ = 8;
         a.n_tiles = count_tiles(p, 32 * NWQ);
         const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
         hipLaunchKernelGGL(bwd_dq_kernel<NWQ>, dim3(grid), dim3(NWQ * 64), 0, s, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (p.stages & STAGE_DKDV) {
+        a.n_tiles = count_tiles(p, 128);
+        const int grid = grid_for_items(a.n_tiles, p.Hkv, p.Hkv);
+        hipLaunchKernelGGL(bwd_dkdv_kernel, dim3(grid), dim3(512), 0, s, a);
         e = hipGetLastError();
     }
     return e;

@@ -1,0 +1,102 @@
+"""GPU parity at the benchmark's full sizes (configs 3, 4 and 5), in the launch
+configuration bench.py times.  The oracle cannot produce whole tensors at these sizes in
+reasonable time, so outputs are sampled: forward rows and dQ rows are independent of each
+other and are recomputed one by one; dK/dV need every row of a kv head, so one kv head of
+one group is recomputed in full."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sp_attn_oracle as orc
+from paper_2511_18871_amd import binding as B
+from paper_2511_18871_amd import workloads as W
+from parity import gate, gate_lse, to64
+
+pytestmark = pytest.mark.gpu
+
+
+def group_slices(w):
+    base = 0
+    for g in w.groups:
+        yield slice(base, base + g.total), g
+        base += g.total
+
+
+def sample_rows(g, rng, n):
+    """Rows that stress every region: first/last prompt rows, rows around the prompt end,
+    first/last row of several responses, plus random ones."""
+    off = [g.prompt_len]
+    for li in g.resp_lens:
+        off.append(off[-1] + li)
+    rows = {0, min(1, g.total - 1), g.prompt_len - 1, g.total - 1}
+    for i in (0, len(g.resp_lens) // 2, len(g.resp_lens) - 1):
+        if g.resp_lens and g.resp_lens[i] > 0:
+            rows |= {off[i], off[i + 1] - 1}
+    rows |= set(int(x) for x in rng.integers(0, g.total, size=n))
+    return sorted(r for r in rows if 0 <= r < g.total)
+
+
+def run_gpu(w, t, backward):
+    q, k, v = t.q.cuda(), t.k.cuda(), t.v.cuda()
+    pl, Gs, rl = w.prompt_lens(), w.Gs(), w.resp_lens_flat()
+    o, lse = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, w.softmax_scale)
+    out = [o, lse]
+    if backward:
+        out += list(B.sp_attn_bwd_batched(q, k, v, o, lse, t.d_o.cuda(), pl, Gs, rl, w.softmax_scale))
+    torch.cuda.synchronize()
+    return [x.cpu() for x in out]
+
+
+def check_sampled(w, t, got, backward, groups, n_rows, heads, kv_check=None):
+    rng = np.random.default_rng(123)
+    for gi, (sl, g) in enumerate(group_slices(w)):
+        if gi not in groups:
+            continue
+        rows = sample_rows(g, rng, n_rows)
+        qg, kg, vg = t.q[sl], t.k[sl], t.v[sl]
+        ro, rlse = orc.sp_attn_fwd(qg, kg, vg, g.prompt_len, g.resp_lens, w.softmax_scale, rows=rows, heads=heads)
+        gate(f"O[g{gi}]", to64(got[0][sl])[rows][:, heads], ro, w.dtype)
+        gate_lse(to64(got[1][:, sl])[heads][:, rows], rlse, w.dtype)
+        if backward:
+            rdq = orc.sp_attn_bwd_rows(qg, kg, vg, t.d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale, rows, heads)
+            gate(f"dQ[g{gi}]", to64(got[2][sl])[rows][:, heads], rdq, w.dtype)
+    if backward and kv_check is not None:
+        gi, kvh = kv_check
+        sl, g = list(group_slices(w))[gi]
+        _, rdk, rdv, _, _ = orc.sp_attn_bwd(t.q[sl], t.k[sl], t.v[sl], t.d_o[sl], g.prompt_len, g.resp_lens,
+                                            w.softmax_scale, kv_heads=[kvh], row_block=2048)
+        gate(f"dK[g{gi},kv{kvh}]", to64(got[3][sl])[:, kvh], rdk[:, kvh], w.dtype)
+        gate(f"dV[g{gi},kv{kvh}]", to64(got[4][sl])[:, kvh], rdv[:, kvh], w.dtype)
+
+
+def test_config3_ragged_multi_group():
+    w = W.config(3)
+    t = W.make_tensors(w)
+    got = run_gpu(w, t, True)
+    check_sampled(w, t, got, True, groups=(0, 3), n_rows=24, heads=[0, 13, 31], kv_check=(1, 5))
+
+
+def test_config4_tri_model_forward_batched_and_per_set():
+    """Three weight sets: run as three calls, and as one call over the 24 concatenated groups."""
+    w = W.config(4)
+    sets = [W.make_tensors(w, s) for s in range(3)]
+    per_set = [run_gpu(w, t, False) for t in sets]
+    for s in (0, 2):
+        check_sampled(w, sets[s], per_set[s], False, groups=(0, 7), n_rows=16, heads=[0, 27])
+    w3 = W.Workload("c4_all_sets", w.groups * 3, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.seed,
+                    backward=False)
+    cat = W.Tensors(torch.cat([t.q for t in sets]), torch.cat([t.k for t in sets]),
+                    torch.cat([t.v for t in sets]), None)
+    o, lse = run_gpu(w3, cat, False)
+    T = w.total_tokens
+    for s in range(3):
+        assert torch.equal(o[s * T:(s + 1) * T], per_set[s][0])
+        assert torch.equal(lse[:, s * T:(s + 1) * T], per_set[s][1])
+
+
+def test_config5_extreme_sharing_large_logits():
+    w = W.config(5)
+    t = W.make_tensors(w)
+    assert len(t.stressed_rows) > 100          # about 1 % of the K rows carry the x8 scale
+    got = run_gpu(w, t, True)
+    check_sampled(w, t, got, True, groups=(0,), n_rows=40, heads=[0, 17, 39], kv_check=(0, 3))
