@@ -42,9 +42,10 @@ def parse_traffic(workload: str, kernel: str):
     return None
 
 
-def cpu_baseline(w, t, target_seconds=20.0):
-    """Time the fp64 oracle (as it stands) on one q head of the workload: forward and
-    backward over all rows of that head.  Useful FLOPs covered = 14 * d * pairs."""
+def cpu_baseline(w, t, target_seconds=12.0):
+    """Time the fp64 oracle (as it stands) on whole q heads of the workload's first group:
+    forward and backward over all rows of each head, one head at a time until about
+    `target_seconds` of CPU work has been done.  Useful FLOPs per head = 14 * d * pairs."""
     import numpy as np
     from oracle import sp_attn_oracle as orc
     from paper_2511_18871_amd import workloads as W
@@ -57,13 +58,17 @@ def cpu_baseline(w, t, target_seconds=20.0):
     n = g.total
     sl = slice(0, n)
     rep = w.n_q_heads // w.n_kv_heads
-    t0 = time.perf_counter()
-    orc.sp_attn_bwd(t.q[sl], t.k[sl], t.v[sl], t.d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale,
-                    kv_heads=[0], q_heads=[0], row_block=1024)
-    dt = time.perf_counter() - t0
-    flops = 14.0 * w.head_dim * W.allowed_pairs(g)
+    d_o = t.d_o if t.d_o is not None else t.q      # forward-only workloads: any upstream gradient
+    heads, dt = 0, 0.0
+    while heads < w.n_q_heads and dt < target_seconds:
+        t0 = time.perf_counter()
+        orc.sp_attn_bwd(t.q[sl], t.k[sl], t.v[sl], d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale,
+                        kv_heads=[heads // rep], q_heads=[heads], row_block=1024)
+        dt += time.perf_counter() - t0
+        heads += 1
+    flops = 14.0 * w.head_dim * W.allowed_pairs(g) * heads
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"q head 0 of {w.n_q_heads} (kv head 0), all {n} rows of group 0, forward+backward in "
+            "sample": f"q heads 0..{heads - 1} of {w.n_q_heads}, all {n} rows of group 0, forward+backward in "
                       f"fp64, {dt:.1f} s",
             "seconds": dt}
 
@@ -76,6 +81,8 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--naive", action="store_true", help="also time the naive packed-causal forward")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
@@ -189,6 +196,13 @@ def main():
         torch.cuda.synchronize()
         nms = evn[0].elapsed_time(evn[1]) / 5
         out["naive_fwd"] = {"ms": round(nms, 4), "useful_tflops": round(fwd_flops / (nms * 1e-3) / 1e12, 2)}
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calib_copy_bytes"] = 1 << 30
 
     if not args.no_cpu:
         out["cpu_baseline"] = {k_: (round(v_, 6) if isinstance(v_, float) else v_)

@@ -275,10 +275,14 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
             async_copy16(src, &ldsKV[ci >> 5][(ci & 31) * 1024]);
         }
     }
-    // asynchronous copy of step `it` = (q head it / nqt, row tile qt0 + it % nqt) into buffer `buf`.
+    // Row tiles are walked from the LAST one down to the workgroup's own keys: workgroups that
+    // start together (they share a kv head and an XCD) then stream the same Q/dO tiles at the
+    // same time, so all but the first read of a tile hit that XCD's L2.
+    // The q heads of the kv head are the inner loop, for the same reason.
+    // asynchronous copy of step `it` = (row tile qt1 - 1 - it / rep, q head it % rep) into buffer `buf`.
     // Rows past the group's end re-read its last row; they are masked (t < e_s <= Tg fails).
     auto issue_tile = [&](int it, int buf) {
-        const int hr = it / nqt, qt = qt0 + it % nqt;
+        const int hr = it % rep, qt = qt1 - 1 - it / rep;
         const int head = kvh * rep + hr;
         const __bf16* qb_ = a.q + ((int64_t)gd.tok_base * a.Hq + head) * 128;
         const __bf16* gb_ = a.d_o + ((int64_t)gd.tok_base * a.Hq + head) * 128;
@@ -309,7 +313,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 
     if (total > 0) issue_tile(0, 0);
     for (int it = 0; it < total; ++it) {
-        const int qt = qt0 + it % nqt;
+        const int qt = qt1 - 1 - it / rep;
         const int buf = it & 1;
         wait_vm0();
         __syncthreads();
