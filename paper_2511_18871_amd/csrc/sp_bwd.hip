@@ -432,7 +432,6 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     a.lse = p.lse; a.D = p.Dbuf; a.L2 = p.Dbuf + (int64_t)p.Hq * p.total_tokens;
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;
     a.tab = p.tab; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
-    constexpr int NW = 4;
     if (p.stages & STAGE_DQ) {
         constexpr int NWQ = 8;
         a.n_tiles = count_tiles(p, 32 * NWQ);

@@ -168,26 +168,6 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// Accumulating MFMA whose accumulator is pinned to the accumulation register file (AGPRs).
-// Kernels that run one wave per SIMD use this for long-lived accumulators that only MFMAs
-// touch, which keeps the compiler from shuttling them through VGPRs.  Back-to-back MFMAs on
-// the same accumulator need no wait states; before the accumulator is read by anything else
-// the caller must let the last MFMA drain (mfma_drain()).
-__device__ __forceinline__ void mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
-    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-// VGPR-accumulator MFMAs written as assembly, for kernels that mix them with AGPR-pinned
-// accumulators (the compiler would otherwise route every MFMA result through AGPRs and copy
-// it back for the vector ALU).  The hardware does not interlock a vector-ALU read of a
-// fresh MFMA result: call mfma_drain() between the last of these and the first such read.
-__device__ __forceinline__ void mfma32_v0(f32x16& acc, bf16x8 a, bf16x8 b) {    // acc = a * b
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma32_v(f32x16& acc, bf16x8 a, bf16x8 b) {     // acc += a * b
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
-
 // Round 8 floats to bf16 (round-to-nearest-even, hardware v_cvt_pk_bf16_f32).
 __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
                                         float a4, float a5, float a6, float a7) {
@@ -222,6 +202,20 @@ __device__ __forceinline__ void async_copy16(const void* gptr, char* lds_base) {
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :: "v"(gptr), "s"(lds_addr) : "memory");
+}
+// Same copy with the global address split into a wave-uniform 64-bit base (scalar registers)
+// and a 32-bit per-lane byte offset, so that a kernel can keep the lane part constant and
+// advance only the scalar base from tile to tile.
+__device__ __forceinline__ void async_copy16_so(const void* sbase, unsigned voff, char* lds_base) {
+    const unsigned lds_addr = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);
+    const uint64_t b = (uint64_t)(uintptr_t)sbase;
+    // readfirstlane returns a signed int: narrow to unsigned before widening, or the low
+    // half would be sign-extended into the high half
+    const uint64_t bs = ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                        (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(bs), "s"(lds_addr) : "memory");
 }
 // 4-byte variant: lane i writes LDS bytes [lds_base + 4*i, +4).
 __device__ __forceinline__ void async_copy4(const void* gptr, char* lds_base) {
