@@ -21,6 +21,7 @@ namespace sp {
 namespace {
 
 constexpr int BN = 64;                 // keys per LDS tile
+constexpr float RESCALE_LOG2 = 8.0f;   // slack of the running softmax reference point, in bits
 constexpr int TILE_BYTES = BN * 256;   // 64 rows x 128 bf16
 
 struct FwdArgs {
@@ -227,7 +228,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         }
         mx = pair_max(mx);
         const float mnew = fmaxf(m, mx);
-        if (__builtin_amdgcn_ballot_w64(mnew > m) != 0) {
+        // The reference point m of a row moves only when its true maximum has outgrown it by
+        // more than 2^RESCALE_LOG2: until then exp2((s - m) c) <= 2^RESCALE_LOG2, which fp32 sums
+        // and bf16 P (relative precision) hold without loss, and the softmax is shift-invariant.
+        // A workgroup advances at the pace of its slowest wave, so making this branch rare
+        // matters more than the work it skips.  (m = -inf: the difference is +inf and it is taken.)
+        if (__builtin_amdgcn_ballot_w64((mnew - m) * cs > RESCALE_LOG2) != 0) {
             const float muse = (mnew == -INFINITY) ? 0.f : mnew;
             const float alpha = __builtin_amdgcn_exp2f((m - muse) * cs);
             lsum *= alpha;
@@ -246,6 +252,9 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #pragma unroll
             for (int i = 0; i < RD - 1; ++i) ring[i] = ldK(ldsK, i);
             __builtin_amdgcn_sched_barrier(0);
+            // the exponentials of sub-block i are consumed (summed, packed) in sub-block i + 1, so
+            // no instruction waits on a transcendental that was issued just before it
+            float pq0 = 0.f, pq1 = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 if (i + RD - 1 < 16) ring[(i + RD - 1) % RD] = ldK(ldsK, i + RD - 1);
@@ -253,11 +262,17 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
                 const int e = 2 * i;
                 const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[e >> 4][e & 15], cs, -mc));
                 const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[e >> 4][(e & 15) + 1], cs, -mc));
-                rowsum += p0 + p1;
-                pbw[i] = pack2(p0, p1);
-                asm volatile("" : "+v"(pbw[i]), "+v"(rowsum));      // keep this slice here
+                if (i > 0) {
+                    rowsum += pq0 + pq1;
+                    pbw[i - 1] = pack2(pq0, pq1);
+                    asm volatile("" : "+v"(pbw[i - 1]), "+v"(rowsum));      // keep this slice here
+                }
+                pq0 = p0; pq1 = p1;
+                asm volatile("" : "+v"(pq0), "+v"(pq1));
                 __builtin_amdgcn_sched_barrier(0);
             }
+            rowsum += pq0 + pq1;
+            pbw[15] = pack2(pq0, pq1);
             lsum += rowsum;
         }
     };
