@@ -37,8 +37,10 @@ struct BwdArgs {
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     constexpr int BM = 32 * NW, BN = 64;
-    constexpr int CH = 32 / NW;                 // 1 KB chunks (4 tile rows) each wave copies per tile
-    __shared__ __attribute__((aligned(1024))) char lds[2][2 * TILE_BYTES];   // [buffer][K | V]
+    constexpr int RD = 3;                       // LDS operand ring depth (prefetch distance RD - 1 MFMAs)
+    constexpr int NE1 = 5;                      // elements of a half's vector work done under the previous D stage
+    static_assert(NW == 8, "the copy split below assumes eight waves");
+    __shared__ __attribute__((aligned(1024))) char lds[3][2 * TILE_BYTES];   // [ring slot][K | V]
 
     int tile, head;
     if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
@@ -59,8 +61,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     const int tw0 = t0 + 32 * w;
     const bool wave_valid = tw0 < Tg;
     const int tw1 = min(tw0 + 31, Tg - 1);
-    const int st_first = wave_valid ? seg_start(gd, tw0) : 0;
-    const int st_last = wave_valid ? seg_start(gd, tw1) : 0;
+    const int st_last = wave_valid ? __builtin_amdgcn_readfirstlane(seg_start(gd, tw1)) : 0;
 
     bf16x8 qreg[8], goreg[8];
     float Lq = 0.f, Dq = 0.f;
@@ -93,20 +94,52 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     const __bf16* kbase = a.k + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
     const __bf16* vbase = a.v + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
 
-    // asynchronous tile copy global -> LDS; rows past the group's end re-read its last row
-    // (those keys are always masked, the values only have to be finite)
-    auto issue_tile = [&](int kt, int buf) {
+    // Tile copy global -> LDS, issued by the first wave of each SIMD (w < 4): those waves are
+    // served first by the instruction arbiter and would otherwise idle at the barrier.  Wave w
+    // copies chunks 4w .. 4w+3 (4 rows each) of the K tile and of the V tile.  Rows past the
+    // group's end re-read its last row (those keys are always masked; values must be finite).
+    const unsigned stride_b = (unsigned)(kv_stride * 2);
+    const bool copier = w < 4;
+    unsigned voff[4];
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int ci = w * CH + u;
-            const int row = 4 * (ci & 15) + (l >> 4);
-            const int gran = (l & 15) ^ swz(row);
-            const int s = min(kt * BN + row, Tg - 1);
-            const __bf16* src = (ci < 16 ? kbase : vbase) + (int64_t)s * kv_stride + gran * 8;
-            async_copy16(src, &lds[buf][(ci >> 4) * TILE_BYTES + (ci & 15) * 1024]);
+    for (int u = 0; u < 4; ++u) {
+        const int row = 4 * (4 * (w & 3) + u) + (l >> 4);
+        voff[u] = row * stride_b + (((l & 15) ^ swz(row)) << 4);
+    }
+    auto sgpr64 = [](const void* p) -> uint64_t {
+        const uint64_t b = (uint64_t)(uintptr_t)p;
+        return ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+               (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    };
+    const uint64_t kbase_s = sgpr64(kbase), vbase_s = sgpr64(vbase);
+    const unsigned tile_bytes = BN * stride_b;
+    auto lds_u32 = [](char* p) -> unsigned {
+        return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)p);
+    };
+    const unsigned m0slot[3] = {lds_u32(lds[0]) + 4096u * (w & 3), lds_u32(lds[1]) + 4096u * (w & 3),
+                                lds_u32(lds[2]) + 4096u * (w & 3)};
+    auto tile_at = [&](int it) { return it < n1 ? it : k2b + (it - n1); };
+    auto issue = [&](int it, int slot) {
+        if (!copier || it >= total) return;
+        const int kt = tile_at(it);
+        const uint64_t off = (uint64_t)(unsigned)kt * tile_bytes;
+        const unsigned m0 = m0slot[slot];
+        if (kt * BN + BN <= Tg) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) async_copy16_sm(kbase_s + off, voff[u], m0 + 1024u * u);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) async_copy16_sm(vbase_s + off, voff[u], m0 + TILE_BYTES + 1024u * u);
+        } else {
+            const int last = Tg - 1 - kt * BN;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int row = 4 * (4 * (w & 3) + u) + (l >> 4);
+                const unsigned vo = min(row, last) * stride_b + (((l & 15) ^ swz(row)) << 4);
+                async_copy16_sm(kbase_s + off, vo, m0 + 1024u * u);
+                async_copy16_sm(vbase_s + off, vo, m0 + TILE_BYTES + 1024u * u);
+            }
         }
     };
-    auto tile_at = [&](int it) { return it < n1 ? it : k2b + (it - n1); };
 
     f32x16 acc[4];
 #pragma unroll
@@ -115,70 +148,136 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     const float cs = a.c;
     float dsum = 0.f;      // sum over this lane's keys of P * dP: an O-free, fp32 evaluation of D
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    if (total > 0) issue_tile(tile_at(0), 0);
-    for (int it = 0; it < total; ++it) {
-        const int kt = tile_at(it);
-        const int buf = it & 1;
-        wait_vm0();
-        __syncthreads();
-        if (it + 1 < total) issue_tile(tile_at(it + 1), buf ^ 1);
-        const char* ldsK = lds[buf];
-        const char* ldsV = lds[buf] + TILE_BYTES;
-
-        const int s0 = kt * BN;
-        const bool skip = !wave_valid || s0 > tw1 || (s0 >= Lp && s0 + BN <= st_first);
-        if (skip) continue;
-
-        f32x16 sacc[2], pacc[2];
+    // Work is cut into halves of 32 keys (two per 64-key tile).  For half h a wave runs
+    //   M(h): S^T, dP^T of the half (16 MFMAs);  V(h): P^T = exp2(S^T c - L), dS^T = P^T (dP^T - D)
+    //   (16 elements of vector work);  D(h): dQ^T += K^T dS^T (8 MFMAs),
+    // software-pipelined so that the vector work always sits between MFMAs of other halves:
+    // V(h) is spread over the slices of D(h-1) (its first NE1 elements) and M(h+1) (the rest).
+    // Each slice is {LDS read for the MFMA RD-1 ahead, one MFMA, a piece of vector work}, fenced.
+    // Masking is done beforehand on S (masked score = -inf gives P = 0 and dS = 0), so the
+    // pipeline body is the same for every tile; the half past the last one is masked whole.
+    const int H = 2 * total;
+    auto s0_of = [&](int h) { return tile_at(h >> 1) * BN + 32 * (h & 1); };
+    auto needs_mask = [&](int h) -> bool {
+        if (h >= H || !wave_valid) return true;
+        const int s0 = s0_of(h);
+        return !((s0 + 31 <= tw0) && (s0 + 32 <= Lp || s0 >= st_last));
+    };
+    auto mask = [&](int h, f32x16& S, f32x16& P) {
+        const bool none = h >= H;
+        const int s0 = none ? 0 : s0_of(h);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int r = 0; r < 16; ++r) {
+            const int key = s0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            const bool ok = !none && key <= tm && (key < Lp || key >= st);
+            S[r] = ok ? S[r] : -INFINITY;
+            P[r] = none ? 0.f : P[r];
+        }
+    };
+    auto ldm = [&](const char* slot, int half, int i) {      // operand i of M: K rows for i < 8 (S), V rows after (dP)
+        return lds_read_row8(slot + ((i & 8) ? TILE_BYTES : 0), 32 * half + c, 2 * (i & 7) + hh);
+    };
+    auto ldd = [&](const char* slot, int half, int i, int part) {   // MFMA i of D: db = i / 2, 16-key step mm = i % 2
+        const int col4 = 32 * (i >> 1) + 16 * c16 + 4 * (j & 3);
+        const int row4 = 32 * half + 16 * (i & 1) + 4 * hh + (j >> 2);
+        return lds_read_tr4(slot, row4 + 8 * part, col4);
+    };
+    auto pack2 = [&](float x, float y) -> unsigned {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 v = {(__bf16)x, (__bf16)y};
+        return __builtin_bit_cast(unsigned, v);
+    };
+    float tprev = 0.f;
+    // vector work on element r: the exponential is issued in one slice and consumed in the next
+    auto v_issue = [&](f32x16& S, int r) {
+        const float tcur = __builtin_amdgcn_exp2f(__builtin_fmaf(S[r], cs, -Lq));
+        return tcur;
+    };
+    auto v_consume = [&](f32x16& S, f32x16& P, int r, float p) {
+        dsum = __builtin_fmaf(p, P[r], dsum);
+        S[r] = p * (P[r] - Dq);
+        asm volatile("" : "+v"(dsum), "+v"(S[r]));
+    };
+    // One pipeline stage for half h: Sc/Pc hold S, dP of half h (elements < NE1 already turned
+    // into dS), Sn/Pn receive half h+1.
+    auto stage = [&](int h, f32x16& Sc, f32x16& Pc, f32x16& Sn, f32x16& Pn,
+                     const char* slotM, int halfM, const char* slotD, int halfD) {
+        unsigned pk[8];
+        {   // M(h+1) with the rest of V(h)
+            bf16x8 ring[RD];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = 0.f; }
+            for (int i = 0; i < RD - 1; ++i) ring[i] = ldm(slotM, halfM, i);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 A = lds_read_row8(ldsK, 32 * kb + c, 2 * ks + hh);
-                sacc[kb] = mfma32(A, qreg[ks], sacc[kb]);
-            }
+            for (int i = 0; i < 16; ++i) {
+                if (i + RD - 1 < 16) ring[(i + RD - 1) % RD] = ldm(slotM, halfM, i + RD - 1);
+                if (i & 8) Pn = mfma32(ring[i % RD], goreg[i & 7], i == 8 ? zero16 : Pn);
+                else Sn = mfma32(ring[i % RD], qreg[i & 7], i == 0 ? zero16 : Sn);
+                float tcur = 0.f;
+                if (NE1 + i < 16) { tcur = v_issue(Sc, NE1 + i); asm volatile("" : "+v"(tcur)); }
+                if (i >= 1 && NE1 + i - 1 < 16) v_consume(Sc, Pc, NE1 + i - 1, tprev);
+                tprev = tcur;
+                if (i >= 12) {
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 A = lds_read_row8(ldsV, 32 * kb + c, 2 * ks + hh);
-                pacc[kb] = mfma32(A, goreg[ks], pacc[kb]);
+                    for (int q = 2 * (i - 12); q < 2 * (i - 12) + 2; ++q) {
+                        pk[q] = pack2(Sc[2 * q], Sc[2 * q + 1]);
+                        asm volatile("" : "+v"(pk[q]));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        const bool full = (s0 + BN - 1 <= tw0) && (s0 + BN <= Lp || s0 >= st_last);
+        if (needs_mask(h + 1)) mask(h + 1, Sn, Pn);
+        __builtin_amdgcn_sched_barrier(0);
+        {   // D(h) with the first NE1 elements of V(h+1)
+            typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+            const bf16x8 db8[2] = {__builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]}),
+                                   __builtin_bit_cast(bf16x8, u32x4{pk[4], pk[5], pk[6], pk[7]})};
+            s16x4 ring[RD][2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int i = 0; i < RD - 1; ++i) { ring[i][0] = ldd(slotD, halfD, i, 0); ring[i][1] = ldd(slotD, halfD, i, 1); }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], cs, -Lq));
-                if (!full) {
-                    const int key = s0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    const bool ok = key <= tm && (key < Lp || key >= st);
-                    p = ok ? p : 0.f;
+            for (int i = 0; i < 8; ++i) {
+                if (i + RD - 1 < 8) {
+                    ring[(i + RD - 1) % RD][0] = ldd(slotD, halfD, i + RD - 1, 0);
+                    ring[(i + RD - 1) % RD][1] = ldd(slotD, halfD, i + RD - 1, 1);
                 }
-                dsum = __builtin_fmaf(p, pacc[kb][r], dsum);
-                sacc[kb][r] = p * (pacc[kb][r] - Dq);     // dS^T
+                acc[i >> 1] = mfma32(cat4(ring[i % RD][0], ring[i % RD][1]), db8[i & 1], acc[i >> 1]);
+                float tcur = 0.f;
+                if (i < NE1) { tcur = v_issue(Sn, i); asm volatile("" : "+v"(tcur)); }
+                if (i >= 1 && i - 1 < NE1) v_consume(Sn, Pn, i - 1, tprev);
+                tprev = tcur;
+                __builtin_amdgcn_sched_barrier(0);
             }
-        bf16x8 db8[2][2];
+        }
+    };
+
+    f32x16 SA, PA, SB, PB;
+    if (total > 0) {
+        issue(0, 0);
+        issue(1, 1);
+        wait_vm0();
+        __syncthreads();
+        // M(0) and the first NE1 elements of V(0), unpipelined
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int i = 0; i < 16; ++i) {
+            if (i & 8) PA = mfma32(ldm(lds[0], 0, i), goreg[i & 7], i == 8 ? zero16 : PA);
+            else SA = mfma32(ldm(lds[0], 0, i), qreg[i & 7], i == 0 ? zero16 : SA);
+        }
+        if (needs_mask(0)) mask(0, SA, PA);
 #pragma unroll
-            for (int mm = 0; mm < 2; ++mm)
-                db8[kb][mm] = pack8(sacc[kb][8 * mm + 0], sacc[kb][8 * mm + 1], sacc[kb][8 * mm + 2],
-                                    sacc[kb][8 * mm + 3], sacc[kb][8 * mm + 4], sacc[kb][8 * mm + 5],
-                                    sacc[kb][8 * mm + 6], sacc[kb][8 * mm + 7]);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const int col4 = 32 * db + 16 * c16 + 4 * (j & 3);
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int mm = 0; mm < 2; ++mm) {
-                    const int row4 = 32 * kb + 16 * mm + 4 * hh + (j >> 2);
-                    const bf16x8 A = cat4(lds_read_tr4(ldsK, row4, col4), lds_read_tr4(ldsK, row4 + 8, col4));
-                    acc[db] = mfma32(A, db8[kb][mm], acc[db]);
-                }
+        for (int r = 0; r < NE1; ++r) v_consume(SA, PA, r, v_issue(SA, r));
+        int slot = 0;
+        for (int it = 0; it < total; ++it) {
+            const int slot1 = slot == 2 ? 0 : slot + 1, slot2 = slot == 0 ? 2 : slot - 1;
+            if (it > 0) { wait_vm0(); __syncthreads(); }
+            issue(it + 2, slot2);           // into the slot of tile it-1, which every wave has left
+            stage(2 * it, SA, PA, SB, PB, lds[slot], 1, lds[slot], 0);
+            stage(2 * it + 1, SB, PB, SA, PA, lds[slot1], 0, lds[slot], 1);
+            slot = slot1;
         }
     }
 

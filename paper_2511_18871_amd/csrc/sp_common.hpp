@@ -217,6 +217,12 @@ __device__ __forceinline__ void async_copy16_so(const void* sbase, unsigned voff
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(bs), "s"(lds_addr) : "memory");
 }
+// Same copy for callers that already hold the base as a 64-bit scalar and the LDS destination
+// as a byte address (both wave-uniform).
+__device__ __forceinline__ void async_copy16_sm(uint64_t sbase, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
 // 4-byte variant: lane i writes LDS bytes [lds_base + 4*i, +4).
 __device__ __forceinline__ void async_copy4(const void* gptr, char* lds_base) {
     const unsigned lds_addr = __builtin_amdgcn_readfirstlane(

@@ -21,7 +21,7 @@ namespace sp {
 namespace {
 
 constexpr int BN = 64;                 // keys per LDS tile
-constexpr float RESCALE_LOG2 = 8.0f;   // slack of the running softmax reference point, in bits
+constexpr float P_LIMIT = 16384.0f;     // bound on a lane's per-tile sum of exponentials (2^14)
 constexpr int TILE_BYTES = BN * 256;   // 64 rows x 128 bf16
 
 struct FwdArgs {
@@ -105,30 +105,46 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     const __bf16* kbase = a.k + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
     const __bf16* vbase = a.v + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
 
-    // Tile copy global -> LDS: each wave copies chunks 2w, 2w+1 (4 rows each) of a 64-row tile.
-    // The per-lane byte offset inside a tile is constant; only the scalar tile base moves.  The
-    // tile that crosses the end of the group re-reads the group's last row for the rows past it.
+    // Tile copy global -> LDS.  The first wave of each SIMD (w < 4) is served first by the
+    // instruction arbiter and reaches the workgroup barrier well ahead of its partner, so those
+    // four waves issue all the copies: wave w copies chunks 4w .. 4w+3 (4 rows each) of a 64-row
+    // tile.  The per-lane byte offset inside a tile is constant; only the scalar tile base moves.
+    // The tile that crosses the end of the group re-reads the group's last row for the rows past it.
     const unsigned stride_b = (unsigned)(kv_stride * 2);
-    unsigned voff[2];
+    const bool copier = w < 4;
+    unsigned voff[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int row = 4 * (2 * w + u) + (l >> 4);
+    for (int u = 0; u < 4; ++u) {
+        const int row = 4 * (4 * (w & 3) + u) + (l >> 4);
         voff[u] = row * stride_b + (((l & 15) ^ swz(row)) << 4);
     }
-    auto issue = [&](const __bf16* base, char* dst, int it) {
-        if (it < 0 || it >= total) return;
+    auto sgpr64 = [](const void* p) -> uint64_t {       // a wave-uniform pointer, kept in scalar registers
+        const uint64_t b = (uint64_t)(uintptr_t)p;
+        return ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+               (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    };
+    const uint64_t kbase_s = sgpr64(kbase), vbase_s = sgpr64(vbase);
+    const unsigned tile_bytes = BN * stride_b;
+    auto lds_u32 = [](char* p) -> unsigned {
+        return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)p);
+    };
+    const unsigned chunk0 = 4096u * (w & 3);
+    const unsigned m0K[2] = {lds_u32(ldsKb[0]) + chunk0, lds_u32(ldsKb[1]) + chunk0};
+    const unsigned m0V[2] = {lds_u32(ldsVb[0]) + chunk0, lds_u32(ldsVb[1]) + chunk0};
+    auto issue = [&](uint64_t base_s, unsigned m0dst, int it) {
+        if (!copier || it >= total) return;
         const int kt = tile_at(it);
-        const char* tbase = reinterpret_cast<const char*>(base) + (int64_t)kt * BN * stride_b;
+        const uint64_t tb = base_s + (uint64_t)(unsigned)kt * tile_bytes;
         if (kt * BN + BN <= Tg) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) async_copy16_so(tbase, voff[u], dst + (2 * w + u) * 1024);
+            for (int u = 0; u < 4; ++u) async_copy16_sm(tb, voff[u], m0dst + 1024u * u);
         } else {
             const int last = Tg - 1 - kt * BN;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int row = 4 * (2 * w + u) + (l >> 4);
+            for (int u = 0; u < 4; ++u) {
+                const int row = 4 * (4 * (w & 3) + u) + (l >> 4);
                 const unsigned vo = min(row, last) * stride_b + (((l & 15) ^ swz(row)) << 4);
-                async_copy16_so(tbase, vo, dst + (2 * w + u) * 1024);
+                async_copy16_sm(tb, vo, m0dst + 1024u * u);
             }
         }
     };
@@ -148,7 +164,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) pbw[i] = 0u;
-    float m = -INFINITY, lsum = 0.f;
+    float m = -INFINITY, lsum = 0.f, lsr = 0.f;
     const float cs = a.c;
     const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
@@ -156,15 +172,20 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     auto ldK = [&](const char* ldsK, int i) -> bf16x8 {         // MFMA i of QK: kb = i / 8, ks = i % 8
         return lds_read_row8(ldsK, 32 * (i >> 3) + c, 2 * (i & 7) + hh);
     };
-    auto ldV = [&](const char* ldsV, int i, int half) -> s16x4 { // MFMA i of PV: db = i / 4, kb = (i / 2) % 2, mm = i % 2
-        const int col4 = 32 * (i >> 2) + 16 * c16 + 4 * (j16 & 3);
-        const int row4 = 32 * ((i >> 1) & 1) + 16 * (i & 1) + 4 * hh + (j16 >> 2) + 8 * half;
+    auto ldV = [&](const char* ldsV, int i, int half) -> s16x4 { // MFMA i of PV: kb = i / 8, mm = (i / 4) % 2, db = i % 4
+        const int col4 = 32 * (i & 3) + 16 * c16 + 4 * (j16 & 3);
+        const int row4 = 32 * (i >> 3) + 16 * ((i >> 2) & 1) + 4 * hh + (j16 >> 2) + 8 * half;
         return lds_read_tr4(ldsV, row4, col4);
     };
     auto pbop = [&](int kb, int mm) -> bf16x8 {
         typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
         u32x4 x = {pbw[8 * kb + 4 * mm], pbw[8 * kb + 4 * mm + 1], pbw[8 * kb + 4 * mm + 2], pbw[8 * kb + 4 * mm + 3]};
         return __builtin_bit_cast(bf16x8, x);
+    };
+    auto sum2 = [&](unsigned packed, float acc) -> float {       // acc + both bf16 halves of `packed`
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), one, acc, false);
     };
     auto pack2 = [&](float x, float y) -> unsigned {
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -181,7 +202,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     auto pv_plain = [&](const char* ldsV) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-            oacc[i >> 2] = mfma32(cat4(ldV(ldsV, i, 0), ldV(ldsV, i, 1)), pbop((i >> 1) & 1, i & 1), oacc[i >> 2]);
+            oacc[i & 3] = mfma32(cat4(ldV(ldsV, i, 0), ldV(ldsV, i, 1)), pbop(i >> 3, (i >> 2) & 1), oacc[i & 3]);
     };
     auto mask = [&](int it, f32x16 (&S)[2]) {
         const int s0 = it < total ? tile_at(it) * BN : 0;
@@ -200,19 +221,40 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // Every wave runs every step: tiles it cannot see are handled by the mask (P = 0), the
     // first step multiplies the zero P against a zero-filled V buffer, and the last step's
     // S(j+1) is computed from a stale K buffer and never used.
+    //
+    // The exponentials of S(j) are taken against the reference point m that the row had BEFORE
+    // this tile, so they do not wait for the tile's row maximum and can be spread evenly, one
+    // element per MFMA slice, over the 32 MFMAs of the step (16 of O += V(j-1) P(j-1), then 16
+    // of S(j+1) = K(j+1) Q^T).  The softmax is shift-invariant, so any finite reference gives
+    // the same O and LSE; what has to hold is that the exponentials stay in range.  That is
+    // checked after the fact: if a lane's 32 exponentials sum to more than P_LIMIT = 2^14 (or
+    // to inf/NaN), the wave takes the exact row maximum as the new reference, rescales O and
+    // the row sum, and recomputes this tile's P -- a rare path, taken a few times per row.
     auto step = [&](int j, auto par_tag, f32x16 (&Scur)[2], f32x16 (&Snext)[2]) {
         constexpr int PAR = decltype(par_tag)::value;
         wait_vm0();
         __syncthreads();
-        issue(vbase, ldsVb[PAR], j);
-        issue(kbase, ldsKb[PAR], j + 2);
+        issue(vbase_s, m0V[PAR], j);
+        issue(kbase_s, m0K[PAR], j + 2);
         const char* ldsV = ldsVb[PAR ^ 1];      // V(j-1)
         const char* ldsK = ldsKb[PAR ^ 1];      // K(j+1)
         if (needs_mask(j)) mask(j, Scur);
         __builtin_amdgcn_sched_barrier(0);
-        // ---- block M: O += V(j-1) P(j-1) with the row max of S(j)
-        float mx = Scur[0][0];
-        {
+        const float mc = m * cs;
+        float tsum = 0.f;          // this lane's half of the tile's row sum
+        float tsr = 0.f;           // the same sum over the bf16-rounded exponentials (what the MFMA multiplies V by)
+        unsigned pnew[16];
+        float pe[32];
+        // vector-ALU slice e: exponential of element e; the sum and the bf16 packing consume
+        // elements issued in earlier slices, so nothing waits on a transcendental just issued
+        auto valu = [&](int e) {
+            pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[e >> 4][e & 15], cs, -mc));
+            asm volatile("" : "+v"(pe[e]));
+            if (e >= 1) { tsum += pe[e - 1]; asm volatile("" : "+v"(tsum)); }
+            if (e >= 2 && (e & 1) == 0) { pnew[(e - 2) >> 1] = pack2(pe[e - 2], pe[e - 1]); asm volatile("" : "+v"(pnew[(e - 2) >> 1])); }
+            if (e >= 3 && (e & 1) == 1) { tsr = sum2(pnew[(e - 3) >> 1], tsr); asm volatile("" : "+v"(tsr)); }
+        };
+        {   // O^T += V(j-1)^T P(j-1)^T, P operand outermost so that its registers die early
             s16x4 ring[RD][2];
 #pragma unroll
             for (int i = 0; i < RD - 1; ++i) { ring[i][0] = ldV(ldsV, i, 0); ring[i][1] = ldV(ldsV, i, 1); }
@@ -220,71 +262,75 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 if (i + RD - 1 < 16) { ring[(i + RD - 1) % RD][0] = ldV(ldsV, i + RD - 1, 0); ring[(i + RD - 1) % RD][1] = ldV(ldsV, i + RD - 1, 1); }
-                oacc[i >> 2] = mfma32(cat4(ring[i % RD][0], ring[i % RD][1]), pbop((i >> 1) & 1, i & 1), oacc[i >> 2]);
-                mx = fmaxf(mx, fmaxf(Scur[(2 * i) >> 4][(2 * i) & 15], Scur[(2 * i + 1) >> 4][(2 * i + 1) & 15]));
-                asm volatile("" : "+v"(mx));                        // keep this slice here
+                oacc[i & 3] = mfma32(cat4(ring[i % RD][0], ring[i % RD][1]), pbop(i >> 3, (i >> 2) & 1), oacc[i & 3]);
+                valu(i);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        mx = pair_max(mx);
-        const float mnew = fmaxf(m, mx);
-        // The reference point m of a row moves only when its true maximum has outgrown it by
-        // more than 2^RESCALE_LOG2: until then exp2((s - m) c) <= 2^RESCALE_LOG2, which fp32 sums
-        // and bf16 P (relative precision) hold without loss, and the softmax is shift-invariant.
-        // A workgroup advances at the pace of its slowest wave, so making this branch rare
-        // matters more than the work it skips.  (m = -inf: the difference is +inf and it is taken.)
-        if (__builtin_amdgcn_ballot_w64((mnew - m) * cs > RESCALE_LOG2) != 0) {
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = __builtin_amdgcn_exp2f((m - muse) * cs);
+        {   // S(j+1) = K(j+1) Q^T
+            bf16x8 ring[RD];
+#pragma unroll
+            for (int i = 0; i < RD - 1; ++i) ring[i] = ldK(ldsK, i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (i + RD - 1 < 16) ring[(i + RD - 1) % RD] = ldK(ldsK, i + RD - 1);
+                Snext[i >> 3] = mfma32(ring[i % RD], qreg[i & 7], (i & 7) == 0 ? zero16 : Snext[i >> 3]);
+                valu(16 + i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        tsum += pe[31];
+        pnew[15] = pack2(pe[30], pe[31]);
+        tsr = sum2(pnew[15], tsr);
+        if (__builtin_amdgcn_ballot_w64(!(tsum <= P_LIMIT)) != 0) {
+            float mx = Scur[0][0];
+#pragma unroll
+            for (int e = 1; e < 32; ++e) mx = fmaxf(mx, Scur[e >> 4][e & 15]);
+            mx = pair_max(mx);
+            const float mnew = fmaxf(m, mx);          // m is always finite
+            const float alpha = __builtin_amdgcn_exp2f((m - mnew) * cs);
             lsum *= alpha;
+            lsr *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
             m = mnew;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- block E: S(j+1) = K(j+1) Q^T with exp2 / row sum / bf16 packing of S(j)
-        {
-            const float mc = ((m == -INFINITY) ? 0.f : m) * cs;
-            float rowsum = 0.f;
-            bf16x8 ring[RD];
+            const float mc2 = mnew * cs;
+            tsum = 0.f;
+            tsr = 0.f;
 #pragma unroll
-            for (int i = 0; i < RD - 1; ++i) ring[i] = ldK(ldsK, i);
-            __builtin_amdgcn_sched_barrier(0);
-            // the exponentials of sub-block i are consumed (summed, packed) in sub-block i + 1, so
-            // no instruction waits on a transcendental that was issued just before it
-            float pq0 = 0.f, pq1 = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (i + RD - 1 < 16) ring[(i + RD - 1) % RD] = ldK(ldsK, i + RD - 1);
-                Snext[i >> 3] = mfma32(ring[i % RD], qreg[i & 7], (i & 7) == 0 ? zero16 : Snext[i >> 3]);
-                const int e = 2 * i;
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[e >> 4][e & 15], cs, -mc));
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[e >> 4][(e & 15) + 1], cs, -mc));
-                if (i > 0) {
-                    rowsum += pq0 + pq1;
-                    pbw[i - 1] = pack2(pq0, pq1);
-                    asm volatile("" : "+v"(pbw[i - 1]), "+v"(rowsum));      // keep this slice here
-                }
-                pq0 = p0; pq1 = p1;
-                asm volatile("" : "+v"(pq0), "+v"(pq1));
-                __builtin_amdgcn_sched_barrier(0);
+            for (int q = 0; q < 16; ++q) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[q >> 3][(2 * q) & 15], cs, -mc2));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[q >> 3][((2 * q) & 15) + 1], cs, -mc2));
+                tsum += p0 + p1;
+                pnew[q] = pack2(p0, p1);
+                tsr = sum2(pnew[q], tsr);
             }
-            rowsum += pq0 + pq1;
-            pbw[15] = pack2(pq0, pq1);
-            lsum += rowsum;
         }
+        lsum += tsum;
+        lsr += tsr;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) pbw[q] = pnew[q];
     };
 
     // zero-fill the V buffer that the first step multiplies against P = 0
     for (int i = tid; i < TILE_BYTES / 16; i += 512)
         reinterpret_cast<i32x4*>(ldsVb[1])[i] = i32x4{0, 0, 0, 0};
-    issue(kbase, ldsKb[0], 0);
-    issue(kbase, ldsKb[1], 1);
+    issue(kbase_s, m0K[0], 0);
+    issue(kbase_s, m0K[1], 1);
     wait_vm0();
     __syncthreads();
     qk_plain(ldsKb[0], sA);
+    {   // exact row maximum of the first tile as the initial reference point
+        if (needs_mask(0)) mask(0, sA);
+        float mx = sA[0][0];
+#pragma unroll
+        for (int e = 1; e < 32; ++e) mx = fmaxf(mx, sA[e >> 4][e & 15]);
+        mx = pair_max(mx);
+        m = (mx == -INFINITY) ? 0.f : mx;      // rows that see nothing in this tile start from 0
+    }
     const int total2 = (total + 1) & ~1;
     for (int j = 0; j < total2; j += 2) {
         step(j, std::integral_constant<int, 0>{}, sA, sB);
@@ -294,9 +340,13 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     __syncthreads();
     pv_plain(ldsVb[1]);                    // P of step total2 - 1 (odd parity)
 
+    // O is normalised by the sum of the ROUNDED weights, the ones V was actually multiplied by:
+    // a row dominated by one key then returns that key's V exactly, whatever the reference point.
+    // LSE uses the unrounded sum.
     const float ltot = pair_sum(lsum);
+    const float lrt = pair_sum(lsr);
     if (valid) {
-        const float inv = 1.0f / ltot;
+        const float inv = 1.0f / lrt;
         __bf16* op = a.o + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
 #pragma unroll
         for (int db = 0; db < 4; ++db)

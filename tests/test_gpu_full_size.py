@@ -55,18 +55,18 @@ def check_sampled(w, t, got, backward, groups, n_rows, heads, kv_check=None):
         rows = sample_rows(g, rng, n_rows)
         qg, kg, vg = t.q[sl], t.k[sl], t.v[sl]
         ro, rlse = orc.sp_attn_fwd(qg, kg, vg, g.prompt_len, g.resp_lens, w.softmax_scale, rows=rows, heads=heads)
-        gate(f"O[g{gi}]", to64(got[0][sl])[rows][:, heads], ro, w.dtype)
+        print(gate(f"O[g{gi}]", to64(got[0][sl])[rows][:, heads], ro, w.dtype))
         gate_lse(to64(got[1][:, sl])[heads][:, rows], rlse, w.dtype)
         if backward:
             rdq = orc.sp_attn_bwd_rows(qg, kg, vg, t.d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale, rows, heads)
-            gate(f"dQ[g{gi}]", to64(got[2][sl])[rows][:, heads], rdq, w.dtype)
+            print(gate(f"dQ[g{gi}]", to64(got[2][sl])[rows][:, heads], rdq, w.dtype))
     if backward and kv_check is not None:
         gi, kvh = kv_check
         sl, g = list(group_slices(w))[gi]
         _, rdk, rdv, _, _ = orc.sp_attn_bwd(t.q[sl], t.k[sl], t.v[sl], t.d_o[sl], g.prompt_len, g.resp_lens,
                                             w.softmax_scale, kv_heads=[kvh], row_block=2048)
-        gate(f"dK[g{gi},kv{kvh}]", to64(got[3][sl])[:, kvh], rdk[:, kvh], w.dtype)
-        gate(f"dV[g{gi},kv{kvh}]", to64(got[4][sl])[:, kvh], rdv[:, kvh], w.dtype)
+        print(gate(f"dK[g{gi},kv{kvh}]", to64(got[3][sl])[:, kvh], rdk[:, kvh], w.dtype))
+        print(gate(f"dV[g{gi},kv{kvh}]", to64(got[4][sl])[:, kvh], rdv[:, kvh], w.dtype))
 
 
 def test_config3_ragged_multi_group():
