@@ -310,6 +310,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
 // are added through LDS at the end, in a fixed order.
 __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     constexpr int BNK = 128, BQ = 64;
+    constexpr int RD = 3;      // LDS operand ring depth (prefetch distance RD - 1 MFMAs)
     __shared__ __attribute__((aligned(1024))) char ldsKV[2][BNK * 256];      // [K | V] of the 128 keys
     __shared__ __attribute__((aligned(1024))) char lds[2][2 * TILE_BYTES];   // [buffer][Q | dO]
     __shared__ __attribute__((aligned(256))) float ldsLD[2][2][BQ];          // [buffer][L2 | D][row]
@@ -378,23 +379,51 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     // start together (they share a kv head and an XCD) then stream the same Q/dO tiles at the
     // same time, so all but the first read of a tile hit that XCD's L2.
     // The q heads of the kv head are the inner loop, for the same reason.
-    // asynchronous copy of step `it` = (row tile qt1 - 1 - it / rep, q head it % rep) into buffer `buf`.
+    // Step `it` = (row tile qt1 - 1 - it / rep, q head it % rep).  Its Q/dO tile is copied
+    // asynchronously into buffer it & 1: wave w copies chunks 2w, 2w+1 (4 rows each) of Q and of
+    // dO, from a scalar tile base plus a constant per-lane offset.  (The copies wait on HBM, and a
+    // wave that queues more than a few of them stalls at issue, so all eight waves share them.)
     // Rows past the group's end re-read its last row; they are masked (t < e_s <= Tg fails).
-    auto issue_tile = [&](int it, int buf) {
-        const int hr = it % rep, qt = qt1 - 1 - it / rep;
-        const int head = kvh * rep + hr;
-        const __bf16* qb_ = a.q + ((int64_t)gd.tok_base * a.Hq + head) * 128;
-        const __bf16* gb_ = a.d_o + ((int64_t)gd.tok_base * a.Hq + head) * 128;
+    const unsigned qstride_b = (unsigned)(q_stride * 2);
+    unsigned voff[2];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int ci = w * 4 + u;                  // 0..15 Q, 16..31 dO
-            const int row = 4 * (ci & 15) + (l >> 4);
-            const int gran = (l & 15) ^ swz(row);
-            const int t = min(qt * BQ + row, Tg - 1);
-            const __bf16* src = (ci < 16 ? qb_ : gb_) + (int64_t)t * q_stride + gran * 8;
-            async_copy16(src, &lds[buf][(ci >> 4) * TILE_BYTES + (ci & 15) * 1024]);
+    for (int u = 0; u < 2; ++u) {
+        const int row = 4 * (2 * w + u) + (l >> 4);
+        voff[u] = row * qstride_b + (((l & 15) ^ swz(row)) << 4);
+    }
+    auto sgpr64 = [](const void* p) -> uint64_t {
+        const uint64_t b = (uint64_t)(uintptr_t)p;
+        return ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+               (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    };
+    auto lds_u32 = [](const void* p) -> unsigned {
+        return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)p);
+    };
+    // q head 0 of this kv head, token 0 of the group
+    const uint64_t qbase_s = sgpr64(a.q + ((int64_t)gd.tok_base * a.Hq + (int64_t)kvh * rep) * 128);
+    const uint64_t gbase_s = sgpr64(a.d_o + ((int64_t)gd.tok_base * a.Hq + (int64_t)kvh * rep) * 128);
+    const unsigned m0buf[2] = {lds_u32(lds[0]) + 2048u * w, lds_u32(lds[1]) + 2048u * w};
+    const unsigned tile_bytes = BQ * qstride_b;
+    auto issue_tile = [&](int qt, int hr, int buf) {
+        const uint64_t off = (uint64_t)(unsigned)qt * tile_bytes + (unsigned)hr * 256u;
+        const unsigned m0 = m0buf[buf];
+        if (qt * BQ + BQ <= Tg) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) async_copy16_sm(qbase_s + off, voff[u], m0 + 1024u * u);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) async_copy16_sm(gbase_s + off, voff[u], m0 + TILE_BYTES + 1024u * u);
+        } else {
+            const int last = Tg - 1 - qt * BQ;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int row = 4 * (2 * w + u) + (l >> 4);
+                const unsigned vo = min(row, last) * qstride_b + (((l & 15) ^ swz(row)) << 4);
+                async_copy16_sm(qbase_s + off, vo, m0 + 1024u * u);
+                async_copy16_sm(gbase_s + off, vo, m0 + TILE_BYTES + 1024u * u);
+            }
         }
-        if (w < 2) {        // wave 0: scaled LSE of the 64 rows, wave 1: D
+        if (w < 2) {        // wave 0: scaled LSE of the 64 rows, wave 1: D (the first wave of a SIMD has slack)
+            const int head = kvh * rep + hr;
             const int t = min(qt * BQ + l, Tg - 1);
             const float* src = (w == 0 ? a.L2 : a.D) + (int64_t)head * T_total + gd.tok_base + t;
             async_copy4(src, reinterpret_cast<char*>(&ldsLD[buf][w][0]));
@@ -409,76 +438,162 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     const float cs = a.c;
     const char* ldsK = ldsKV[0];
     const char* ldsV = ldsKV[1];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto pack2 = [&](float x, float y) -> unsigned {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 v = {(__bf16)x, (__bf16)y};
+        return __builtin_bit_cast(unsigned, v);
+    };
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
-    if (total > 0) issue_tile(0, 0);
+    // Within a step the vector work is folded under the MFMAs: the exponentials of the first 8
+    // rows run under the dP MFMAs (S is complete by then), those of the last 8 rows under the
+    // first half of the dV/dK MFMAs (which only need the first 8 rows of P and dS).  Masking is
+    // applied to S beforehand (score -inf gives P = 0 and dS = 0).
+    int qt = qt1 - 1, hr = 0;                 // step 0
+    int qt_n = qt, hr_n = 1;                  // step 1
+    if (hr_n == rep) { hr_n = 0; --qt_n; }
+    if (total > 0) issue_tile(qt, hr, 0);
     for (int it = 0; it < total; ++it) {
-        const int qt = qt1 - 1 - it / rep;
         const int buf = it & 1;
         wait_vm0();
         __syncthreads();
-        if (it + 1 < total) issue_tile(it + 1, buf ^ 1);
+        if (it + 1 < total) issue_tile(qt_n, hr_n, buf ^ 1);
         const char* ldsQ = lds[buf];
         const char* ldsG = lds[buf] + TILE_BYTES;
         const float* ldsL = ldsLD[buf][0];
         const float* ldsD = ldsLD[buf][1];
-
         const int r0 = qt * BQ + 32 * qh;              // this wave's 32 rows
+        qt = qt_n; hr = hr_n;
+        if (++hr_n == rep) { hr_n = 0; --qt_n; }
         // no row of this wave's half sees any key of this wave
         const bool skip = !wave_valid || r0 + 31 < ws0 || r0 >= e_max;
         if (skip) continue;
 
         f32x16 sacc, pacc;
+        {   // S = Q K^T
+            bf16x8 ra[RD], rb[RD];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+            for (int i = 0; i < RD - 1; ++i) {
+                ra[i] = lds_read_row8(ldsQ, 32 * qh + c, 2 * i + hh);
+                rb[i] = lds_read_row8(ldsK, 32 * kb + c, 2 * i + hh);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 A = lds_read_row8(ldsQ, 32 * qh + c, 2 * ks + hh);
-            const bf16x8 Bk = lds_read_row8(ldsK, 32 * kb + c, 2 * ks + hh);
-            sacc = mfma32(A, Bk, sacc);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 A = lds_read_row8(ldsG, 32 * qh + c, 2 * ks + hh);
-            const bf16x8 Bv = lds_read_row8(ldsV, 32 * kb + c, 2 * ks + hh);
-            pacc = mfma32(A, Bv, pacc);
+            for (int i = 0; i < 8; ++i) {
+                if (i + RD - 1 < 8) {
+                    ra[(i + RD - 1) % RD] = lds_read_row8(ldsQ, 32 * qh + c, 2 * (i + RD - 1) + hh);
+                    rb[(i + RD - 1) % RD] = lds_read_row8(ldsK, 32 * kb + c, 2 * (i + RD - 1) + hh);
+                }
+                sacc = mfma32(ra[i % RD], rb[i % RD], i == 0 ? zero16 : sacc);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         // every row of the half sees every key of the wave
         const bool full = r0 >= ws1 && ws0 + 31 < Tg && r0 + 32 <= e_min;
+        if (!full) {
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const int rr = 32 * qh + 8 * gq + 4 * hh;
-            const f32x4 L4 = *reinterpret_cast<const f32x4*>(&ldsL[rr]);
-            const f32x4 D4 = *reinterpret_cast<const f32x4*>(&ldsD[rr]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int r = 4 * gq + e;
-                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], cs, -L4[e]));
-                if (!full) {
-                    const int t = qt * BQ + rr + e;
-                    p = (t >= s && t < e_s) ? p : 0.f;
-                }
-                sacc[r] = p;                              // P
-                pacc[r] = p * (pacc[r] - D4[e]);          // dS
+            for (int r = 0; r < 16; ++r) {
+                const int t = r0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+                sacc[r] = (t >= s && t < e_s) ? sacc[r] : -INFINITY;
             }
         }
-        bf16x8 p8[2], d8[2];
+        __builtin_amdgcn_sched_barrier(0);
+        float Lr[16], Dr[16];
+        {   // dP = dO V^T, with the exponentials of rows 0..7 of the block
+            bf16x8 ra[RD], rb[RD];
 #pragma unroll
-        for (int mm = 0; mm < 2; ++mm) {
-            p8[mm] = pack8(sacc[8 * mm + 0], sacc[8 * mm + 1], sacc[8 * mm + 2], sacc[8 * mm + 3],
-                           sacc[8 * mm + 4], sacc[8 * mm + 5], sacc[8 * mm + 6], sacc[8 * mm + 7]);
-            d8[mm] = pack8(pacc[8 * mm + 0], pacc[8 * mm + 1], pacc[8 * mm + 2], pacc[8 * mm + 3],
-                           pacc[8 * mm + 4], pacc[8 * mm + 5], pacc[8 * mm + 6], pacc[8 * mm + 7]);
+            for (int i = 0; i < RD - 1; ++i) {
+                ra[i] = lds_read_row8(ldsG, 32 * qh + c, 2 * i + hh);
+                rb[i] = lds_read_row8(ldsV, 32 * kb + c, 2 * i + hh);
+            }
+#pragma unroll
+            for (int gq = 0; gq < 2; ++gq) {
+                const f32x4 L4 = *reinterpret_cast<const f32x4*>(&ldsL[32 * qh + 8 * gq + 4 * hh]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) Lr[4 * gq + e] = L4[e];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i + RD - 1 < 8) {
+                    ra[(i + RD - 1) % RD] = lds_read_row8(ldsG, 32 * qh + c, 2 * (i + RD - 1) + hh);
+                    rb[(i + RD - 1) % RD] = lds_read_row8(ldsV, 32 * kb + c, 2 * (i + RD - 1) + hh);
+                }
+                if (i == 2 || i == 3) {         // D of rows 0..7, L of rows 8..15
+                    const f32x4 D4 = *reinterpret_cast<const f32x4*>(&ldsD[32 * qh + 8 * (i - 2) + 4 * hh]);
+                    const f32x4 L4 = *reinterpret_cast<const f32x4*>(&ldsL[32 * qh + 8 * i + 4 * hh]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { Dr[4 * (i - 2) + e] = D4[e]; Lr[4 * i + e] = L4[e]; }
+                }
+                pacc = mfma32(ra[i % RD], rb[i % RD], i == 0 ? zero16 : pacc);
+                sacc[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], cs, -Lr[i]));      // P
+                asm volatile("" : "+v"(sacc[i]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        unsigned pp[8], dd[8];       // packed bf16 pairs of P and dS: [4 * mm + r / 2]
+#pragma unroll
+        for (int r = 0; r < 8; ++r) pacc[r] = sacc[r] * (pacc[r] - Dr[r]);               // dS
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { pp[q] = pack2(sacc[2 * q], sacc[2 * q + 1]); dd[q] = pack2(pacc[2 * q], pacc[2 * q + 1]); }
+        __builtin_amdgcn_sched_barrier(0);
+        // dV^T += dO^T P, dK^T += Q^T dS.  MFMA i of a half: db = i / 2, dV for even i, dK for odd i.
+        auto ldt = [&](int mm, int i, int part) {
+            const int col4 = 32 * (i >> 1) + 16 * c16 + 4 * (j & 3);
+            const int row4 = 32 * qh + 16 * mm + 4 * hh + (j >> 2);
+            return lds_read_tr4((i & 1) ? ldsQ : ldsG, row4 + 8 * part, col4);
+        };
+        {   // first 16 rows of the block (mm = 0), with the exponentials and dS of rows 8..15
+            const bf16x8 p8 = __builtin_bit_cast(bf16x8, u32x4{pp[0], pp[1], pp[2], pp[3]});
+            const bf16x8 d8 = __builtin_bit_cast(bf16x8, u32x4{dd[0], dd[1], dd[2], dd[3]});
+            s16x4 ring[RD][2];
+#pragma unroll
+            for (int i = 0; i < RD - 1; ++i) { ring[i][0] = ldt(0, i, 0); ring[i][1] = ldt(0, i, 1); }
+#pragma unroll
+            for (int gq = 2; gq < 4; ++gq) {
+                const f32x4 D4 = *reinterpret_cast<const f32x4*>(&ldsD[32 * qh + 8 * gq + 4 * hh]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) Dr[4 * gq + e] = D4[e];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            float tprev = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i + RD - 1 < 8) { ring[(i + RD - 1) % RD][0] = ldt(0, i + RD - 1, 0); ring[(i + RD - 1) % RD][1] = ldt(0, i + RD - 1, 1); }
+                const bf16x8 A = cat4(ring[i % RD][0], ring[i % RD][1]);
+                if (i & 1) dkacc[i >> 1] = mfma32(A, d8, dkacc[i >> 1]);
+                else dvacc[i >> 1] = mfma32(A, p8, dvacc[i >> 1]);
+                float tcur = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 + i], cs, -Lr[8 + i]));
+                asm volatile("" : "+v"(tcur));
+                if (i >= 1) {
+                    sacc[8 + i - 1] = tprev;
+                    pacc[8 + i - 1] = tprev * (pacc[8 + i - 1] - Dr[8 + i - 1]);
+                    asm volatile("" : "+v"(pacc[8 + i - 1]));
+                }
+                tprev = tcur;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sacc[15] = tprev;
+            pacc[15] = tprev * (pacc[15] - Dr[15]);
         }
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const int col4 = 32 * db + 16 * c16 + 4 * (j & 3);
+        for (int q = 4; q < 8; ++q) { pp[q] = pack2(sacc[2 * q], sacc[2 * q + 1]); dd[q] = pack2(pacc[2 * q], pacc[2 * q + 1]); }
+        __builtin_amdgcn_sched_barrier(0);
+        {   // last 16 rows of the block (mm = 1)
+            const bf16x8 p8 = __builtin_bit_cast(bf16x8, u32x4{pp[4], pp[5], pp[6], pp[7]});
+            const bf16x8 d8 = __builtin_bit_cast(bf16x8, u32x4{dd[4], dd[5], dd[6], dd[7]});
+            s16x4 ring[RD][2];
 #pragma unroll
-            for (int mm = 0; mm < 2; ++mm) {
-                const int row4 = 32 * qh + 16 * mm + 4 * hh + (j >> 2);
-                const bf16x8 Ag = cat4(lds_read_tr4(ldsG, row4, col4), lds_read_tr4(ldsG, row4 + 8, col4));
-                dvacc[db] = mfma32(Ag, p8[mm], dvacc[db]);
-                const bf16x8 Aq = cat4(lds_read_tr4(ldsQ, row4, col4), lds_read_tr4(ldsQ, row4 + 8, col4));
-                dkacc[db] = mfma32(Aq, d8[mm], dkacc[db]);
+            for (int i = 0; i < RD - 1; ++i) { ring[i][0] = ldt(1, i, 0); ring[i][1] = ldt(1, i, 1); }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i + RD - 1 < 8) { ring[(i + RD - 1) % RD][0] = ldt(1, i + RD - 1, 0); ring[(i + RD - 1) % RD][1] = ldt(1, i + RD - 1, 1); }
+                const bf16x8 A = cat4(ring[i % RD][0], ring[i % RD][1]);
+                if (i & 1) dkacc[i >> 1] = mfma32(A, d8, dkacc[i >> 1]);
+                else dvacc[i >> 1] = mfma32(A, p8, dvacc[i >> 1]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
