@@ -150,20 +150,23 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     };
     // true when some (row, key) pair of this wave in tile `it` is masked; tiles past the end
     // of the key range (the pad step of an odd-length loop) are masked entirely
+    // the first n_full tiles (whole prompt tiles at or below the wave's first row) never need it
+    const int n_full = (!wave_valid || a.naive) ? 0 : __builtin_amdgcn_readfirstlane(min(min(Lp, tw0 + 1) / BN, n1));
     auto needs_mask = [&](int it) -> bool {
+        if (it < n_full) return false;
         if (it >= total || !wave_valid || a.naive) return true;
         const int s0 = tile_at(it) * BN;
         return !((s0 + BN - 1 <= tw0) && (s0 + BN <= Lp || s0 >= st_last));
     };
 
     f32x16 oacc[4], sA[2], sB[2];
-    unsigned pbw[16];          // P of the previous tile as packed bf16 pairs: pbw[8*kb + r/2]
+    unsigned pbA[16], pbB[16]; // P of a tile as packed bf16 pairs, [8*kb + r/2]; the two alternate from step to step
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) pbw[i] = 0u;
+    for (int i = 0; i < 16; ++i) { pbA[i] = 0u; pbB[i] = 0u; }
     float m = -INFINITY, lsum = 0.f, lsr = 0.f;
     const float cs = a.c;
     const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         const int row4 = 32 * (i >> 3) + 16 * ((i >> 2) & 1) + 4 * hh + (j16 >> 2) + 8 * half;
         return lds_read_tr4(ldsV, row4, col4);
     };
-    auto pbop = [&](int kb, int mm) -> bf16x8 {
+    auto pbop = [&](const unsigned (&pbw)[16], int kb, int mm) -> bf16x8 {
         typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
         u32x4 x = {pbw[8 * kb + 4 * mm], pbw[8 * kb + 4 * mm + 1], pbw[8 * kb + 4 * mm + 2], pbw[8 * kb + 4 * mm + 3]};
         return __builtin_bit_cast(bf16x8, x);
@@ -199,10 +202,10 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         for (int i = 0; i < 16; ++i)
             S[i >> 3] = mfma32(ldK(ldsK, i), qreg[i & 7], (i & 7) == 0 ? zero16 : S[i >> 3]);
     };
-    auto pv_plain = [&](const char* ldsV) {
+    auto pv_plain = [&](const char* ldsV, const unsigned (&pbw)[16]) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-            oacc[i & 3] = mfma32(cat4(ldV(ldsV, i, 0), ldV(ldsV, i, 1)), pbop(i >> 3, (i >> 2) & 1), oacc[i & 3]);
+            oacc[i & 3] = mfma32(cat4(ldV(ldsV, i, 0), ldV(ldsV, i, 1)), pbop(pbw, i >> 3, (i >> 2) & 1), oacc[i & 3]);
     };
     auto mask = [&](int it, f32x16 (&S)[2]) {
         const int s0 = it < total ? tile_at(it) * BN : 0;
@@ -230,7 +233,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // checked after the fact: if a lane's 32 exponentials sum to more than P_LIMIT = 2^14 (or
     // to inf/NaN), the wave takes the exact row maximum as the new reference, rescales O and
     // the row sum, and recomputes this tile's P -- a rare path, taken a few times per row.
-    auto step = [&](int j, auto par_tag, f32x16 (&Scur)[2], f32x16 (&Snext)[2]) {
+    auto step = [&](int j, auto par_tag, f32x16 (&Scur)[2], f32x16 (&Snext)[2], const unsigned (&pbw)[16], unsigned (&pnew)[16]) {
         constexpr int PAR = decltype(par_tag)::value;
         wait_vm0();
         __syncthreads();
@@ -243,7 +246,6 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         const float mc = m * cs;
         float tsum = 0.f;          // this lane's half of the tile's row sum
         float tsr = 0.f;           // the same sum over the bf16-rounded exponentials (what the MFMA multiplies V by)
-        unsigned pnew[16];
         float pe[32];
         // vector-ALU slice e: exponential of element e; the sum and the bf16 packing consume
         // elements issued in earlier slices, so nothing waits on a transcendental just issued
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 if (i + RD - 1 < 16) { ring[(i + RD - 1) % RD][0] = ldV(ldsV, i + RD - 1, 0); ring[(i + RD - 1) % RD][1] = ldV(ldsV, i + RD - 1, 1); }
-                oacc[i & 3] = mfma32(cat4(ring[i % RD][0], ring[i % RD][1]), pbop(i >> 3, (i >> 2) & 1), oacc[i & 3]);
+                oacc[i & 3] = mfma32(cat4(ring[i % RD][0], ring[i % RD][1]), pbop(pbw, i >> 3, (i >> 2) & 1), oacc[i & 3]);
                 valu(i);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -311,8 +313,6 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         }
         lsum += tsum;
         lsr += tsr;
-#pragma unroll
-        for (int q = 0; q < 16; ++q) pbw[q] = pnew[q];
     };
 
     // zero-fill the V buffer that the first step multiplies against P = 0
@@ -333,12 +333,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     }
     const int total2 = (total + 1) & ~1;
     for (int j = 0; j < total2; j += 2) {
-        step(j, std::integral_constant<int, 0>{}, sA, sB);
-        step(j + 1, std::integral_constant<int, 1>{}, sB, sA);
+        step(j, std::integral_constant<int, 0>{}, sA, sB, pbA, pbB);
+        step(j + 1, std::integral_constant<int, 1>{}, sB, sA, pbB, pbA);
     }
     wait_vm0();
     __syncthreads();
-    pv_plain(ldsVb[1]);                    // P of step total2 - 1 (odd parity)
+    pv_plain(ldsVb[1], pbA);                    // P of step total2 - 1 (odd parity)
 
     // O is normalised by the sum of the ROUNDED weights, the ones V was actually multiplied by:
     // a row dominated by one key then returns that key's V exactly, whatever the reference point.
