@@ -48,8 +48,8 @@ struct FwdArgs {
 __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     constexpr int BM = 256;
     constexpr int RD = 3;      // LDS operand ring depth (prefetch distance RD - 1 MFMAs)
-    __shared__ __attribute__((aligned(1024))) char ldsKb[2][TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char ldsVb[2][TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char ldsKb[4][TILE_BYTES];      // K tile t lives in ldsKb[t & 3]
+    __shared__ __attribute__((aligned(1024))) char ldsVb[4][TILE_BYTES];      // V tile t in ldsVb[t & 3]
 
     int tile, head;
     if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
@@ -129,8 +129,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)p);
     };
     const unsigned chunk0 = 4096u * (w & 3);
-    const unsigned m0K[2] = {lds_u32(ldsKb[0]) + chunk0, lds_u32(ldsKb[1]) + chunk0};
-    const unsigned m0V[2] = {lds_u32(ldsVb[0]) + chunk0, lds_u32(ldsVb[1]) + chunk0};
+    const unsigned m0K[4] = {lds_u32(ldsKb[0]) + chunk0, lds_u32(ldsKb[1]) + chunk0, lds_u32(ldsKb[2]) + chunk0, lds_u32(ldsKb[3]) + chunk0};
+    const unsigned m0V[4] = {lds_u32(ldsVb[0]) + chunk0, lds_u32(ldsVb[1]) + chunk0, lds_u32(ldsVb[2]) + chunk0, lds_u32(ldsVb[3]) + chunk0};
     auto issue = [&](uint64_t base_s, unsigned m0dst, int it) {
         if (!copier || it >= total) return;
         const int kt = tile_at(it);
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
             }
     };
 
-    // one pipeline step for tile j (parity PAR = j & 1): Scur holds S(j), Snext receives S(j+1).
+    // one pipeline step for tile j (R = j & 3 selects the LDS buffers): Scur holds S(j), Snext receives S(j+1).
     // Every wave runs every step: tiles it cannot see are handled by the mask (P = 0), the
     // first step multiplies the zero P against a zero-filled V buffer, and the last step's
     // S(j+1) is computed from a stale K buffer and never used.
@@ -234,13 +234,9 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // to inf/NaN), the wave takes the exact row maximum as the new reference, rescales O and
     // the row sum, and recomputes this tile's P -- a rare path, taken a few times per row.
     auto step = [&](int j, auto par_tag, f32x16 (&Scur)[2], f32x16 (&Snext)[2], const unsigned (&pbw)[16], unsigned (&pnew)[16]) {
-        constexpr int PAR = decltype(par_tag)::value;
-        wait_vm0();
-        __syncthreads();
-        issue(vbase_s, m0V[PAR], j);
-        issue(kbase_s, m0K[PAR], j + 2);
-        const char* ldsV = ldsVb[PAR ^ 1];      // V(j-1)
-        const char* ldsK = ldsKb[PAR ^ 1];      // K(j+1)
+        constexpr int R = decltype(par_tag)::value;
+        const char* ldsV = ldsVb[(R + 3) & 3];  // V(j-1)
+        const char* ldsK = ldsKb[(R + 1) & 3];  // K(j+1)
         if (needs_mask(j)) mask(j, Scur);
         __builtin_amdgcn_sched_barrier(0);
         const float mc = m * cs;
@@ -315,11 +311,13 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         lsr += tsr;
     };
 
-    // zero-fill the V buffer that the first step multiplies against P = 0
+    // zero-fill the V buffer that the first step multiplies against P = 0 (it stands for V(-1))
     for (int i = tid; i < TILE_BYTES / 16; i += 512)
-        reinterpret_cast<i32x4*>(ldsVb[1])[i] = i32x4{0, 0, 0, 0};
+        reinterpret_cast<i32x4*>(ldsVb[3])[i] = i32x4{0, 0, 0, 0};
     issue(kbase_s, m0K[0], 0);
     issue(kbase_s, m0K[1], 1);
+    issue(kbase_s, m0K[2], 2);
+    issue(vbase_s, m0V[0], 0);
     wait_vm0();
     __syncthreads();
     qk_plain(ldsKb[0], sA);
@@ -331,14 +329,33 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         mx = pair_max(mx);
         m = (mx == -INFINITY) ? 0.f : mx;      // rows that see nothing in this tile start from 0
     }
-    const int total2 = (total + 1) & ~1;
-    for (int j = 0; j < total2; j += 2) {
+    // Two steps per workgroup barrier: with four K and four V buffers the tiles of the next two
+    // steps are copied while these two run.  At the barrier before steps j, j+1 (j even) the tiles
+    // V(j-1), V(j), K(j+1), K(j+2) are resident and V(j+1), V(j+2), K(j+3), K(j+4) are issued into
+    // the four buffers that the previous two steps read last.  The loop is padded to a multiple of
+    // four steps (buffer indices are compile-time); padded steps are fully masked.
+    const int total4 = (total + 3) & ~3;
+    for (int j = 0; j < total4; j += 4) {
+        wait_vm0();
+        __syncthreads();
+        issue(vbase_s, m0V[1], j + 1);
+        issue(vbase_s, m0V[2], j + 2);
+        issue(kbase_s, m0K[3], j + 3);
+        issue(kbase_s, m0K[0], j + 4);
         step(j, std::integral_constant<int, 0>{}, sA, sB, pbA, pbB);
         step(j + 1, std::integral_constant<int, 1>{}, sB, sA, pbB, pbA);
+        wait_vm0();
+        __syncthreads();
+        issue(vbase_s, m0V[3], j + 3);
+        issue(vbase_s, m0V[0], j + 4);
+        issue(kbase_s, m0K[1], j + 5);
+        issue(kbase_s, m0K[2], j + 6);
+        step(j + 2, std::integral_constant<int, 2>{}, sA, sB, pbA, pbB);
+        step(j + 3, std::integral_constant<int, 3>{}, sB, sA, pbB, pbA);
     }
     wait_vm0();
     __syncthreads();
-    pv_plain(ldsVb[1], pbA);                    // P of step total2 - 1 (odd parity)
+    pv_plain(ldsVb[3], pbA);                    // P of step total4 - 1, V(total4 - 1)
 
     // O is normalised by the sum of the ROUNDED weights, the ones V was actually multiplied by:
     // a row dominated by one key then returns that key's V exactly, whatever the reference point.
