@@ -197,6 +197,28 @@ def main():
         nms = evn[0].elapsed_time(evn[1]) / 5
         out["naive_fwd"] = {"ms": round(nms, 4), "useful_tflops": round(fwd_flops / (nms * 1e-3) / 1e12, 2)}
 
+    if w.n_sets > 1:
+        # all weight sets of the workload (policy / old policy / reference) in one launch,
+        # beside n_sets separate launches of the same kernel
+        sets = [t] + [W.make_tensors(w, i) for i in range(1, w.n_sets)]
+        qs, ks, vs = [x.q.to(dev) for x in sets], [x.k.to(dev) for x in sets], [x.v.to(dev) for x in sets]
+        os_ = [torch.empty_like(x) for x in qs]
+        ls_ = [torch.empty(Hq, T, dtype=torch.float32, device=dev) for _ in qs]
+        evm = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        B.sp_attn_fwd_multi(qs, ks, vs, pl, Gs, rl, scale, os=os_, lses=ls_, workspace=ws)
+        evm[0].record()
+        for _ in range(5):
+            B.sp_attn_fwd_multi(qs, ks, vs, pl, Gs, rl, scale, os=os_, lses=ls_, workspace=ws)
+        evm[1].record()
+        for _ in range(5):
+            for i in range(w.n_sets):
+                B.sp_attn_fwd_batched(qs[i], ks[i], vs[i], pl, Gs, rl, scale, o=os_[i], lse=ls_[i], workspace=ws)
+        evm[2].record()
+        torch.cuda.synchronize()
+        mms, sms = evm[0].elapsed_time(evm[1]) / 5, evm[1].elapsed_time(evm[2]) / 5
+        out["multi_set_fwd"] = {"sets": w.n_sets, "one_launch_ms": round(mms, 4), "separate_launches_ms": round(sms, 4),
+                                "tflops": round(fwd_flops * w.n_sets / (mms * 1e-3) / 1e12, 2)}
+
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)

@@ -144,6 +144,28 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
                                      float softmax_scale, sp_dtype dtype, uint32_t stages,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Forward for several tensor sets that share ONE packing, in one launch: the policy, old-policy
+ * and reference models of a GRPO step score the same packed sequences, so their three
+ * attention forwards differ only in q, k, v (Section 3.2: all log-probabilities of a
+ * micro-step are evaluated together; Section 4.3 packing).  The segment table is built and
+ * uploaded once, the mask classification and the block schedule are shared, and set i's blocks
+ * read q[i], k[i], v[i] and write o[i], lse[i].  Results are bitwise those of n_sets separate
+ * sp_attn_fwd_batched calls.
+ *   n_sets        1 .. SP_MAX_SETS
+ *   q, k, v, o, lse   HOST arrays of n_sets DEVICE pointers (layouts as in sp_attn_fwd);
+ *                 the arrays are read before the call returns
+ *   the rest      as sp_attn_fwd_batched (schedule: shared-prompt).  The workspace is that of
+ *                 one forward: sp_attn_workspace_bytes(0, ...).
+ * Errors as sp_attn_fwd; SP_ERR_INVALID_ARG also for n_sets out of range or a NULL array. */
+#define SP_MAX_SETS 4
+sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* const* k,
+                            const void* const* v, void* const* o, float* const* lse,
+                            int32_t n_groups, const int32_t* prompt_lens,
+                            const int32_t* Gs, const int32_t* resp_lens_flat,
+                            int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                            float softmax_scale, sp_dtype dtype,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Text of the most recent error on the calling thread ("" if none).  The pointer
  * refers to thread-local static storage; the caller must not free it. */
 const char* sp_attn_last_error(void);

@@ -21,7 +21,8 @@ SP_SCHED_SHARED, SP_SCHED_NAIVE_CAUSAL = 0, 1
 SP_BWD_STAGE_ROWSUM, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2, 4, 7
 
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
-           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_last_error", "sp_attn_version")
+           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_last_error",
+           "sp_attn_version")
 
 _lib = None
 
@@ -59,6 +60,9 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_bwd_batched_stages.restype = ctypes.c_int
     lib.sp_attn_bwd_batched_stages.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32,
                                                f32, ctypes.c_int, ctypes.c_uint32, vp, sz, vp]
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    lib.sp_attn_fwd_multi.restype = ctypes.c_int
+    lib.sp_attn_fwd_multi.argtypes = [i32, pp, pp, pp, pp, pp, i32, ip, ip, ip, i32, i32, i32, f32, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
     lib.sp_attn_last_error.argtypes = []
     lib.sp_attn_version.restype = ctypes.c_char_p
@@ -150,6 +154,23 @@ def sp_attn_fwd_batched(q, k, v, prompt_lens: Sequence[int], Gs: Sequence[int], 
                                    softmax_scale, _dtype_code(q), schedule, workspace.data_ptr(),
                                    workspace.numel(), _stream_ptr(stream)))
     return o, lse
+
+
+def sp_attn_fwd_multi(qs, ks, vs, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int],
+                      softmax_scale: float, os=None, lses=None, workspace=None, stream=None):
+    """Forward of several (q, k, v) sets that share one packing, in one launch.  Returns (os, lses)."""
+    lib = load_library()
+    n = len(qs)
+    T, Hq, d = qs[0].shape
+    Hkv = ks[0].shape[1]
+    os = [torch.empty_like(q) for q in qs] if os is None else os
+    lses = [torch.empty(Hq, T, dtype=torch.float32, device=qs[0].device) for _ in qs] if lses is None else lses
+    workspace = _workspace(False, qs[0], len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    arr = lambda ts: (ctypes.c_void_p * max(1, len(ts)))(*[t.data_ptr() for t in ts])
+    _check(lib.sp_attn_fwd_multi(n, arr(qs), arr(ks), arr(vs), arr(os), arr(lses), len(prompt_lens),
+                                 _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
+                                 _dtype_code(qs[0]), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return os, lses
 
 
 def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],

@@ -203,6 +203,56 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
                workspace_bytes, stream);
 }
 
+sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* const* k, const void* const* v,
+                            void* const* o, float* const* lse, int32_t n_groups, const int32_t* prompt_lens,
+                            const int32_t* Gs, const int32_t* resp_lens_flat, int32_t n_q_heads, int32_t n_kv_heads,
+                            int32_t head_dim, float softmax_scale, sp_dtype dtype, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    if (n_sets < 1 || n_sets > SP_MAX_SETS)
+        return fail(SP_ERR_INVALID_ARG, "n_sets=%d is outside 1..%d", n_sets, SP_MAX_SETS);
+    if (!q || !k || !v || !o || !lse) return fail(SP_ERR_INVALID_ARG, "a pointer array is NULL");
+    sp_status st = check_geometry(n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype);
+    if (st != SP_OK) return st;
+    for (int i = 0; i < n_sets; ++i) {
+        const void* ptrs[] = {q[i], k[i], v[i], o[i], lse[i]};
+        for (const void* p : ptrs) {
+            if (!p) return fail(SP_ERR_INVALID_ARG, "set %d: a tensor pointer is NULL", i);
+            if (misaligned(p)) return fail(SP_ERR_INVALID_ARG, "set %d: tensor pointer %p is not 16-byte aligned", i, p);
+        }
+    }
+    Layout L;
+    st = build_table(n_groups, prompt_lens, Gs, resp_lens_flat, L);
+    if (st != SP_OK) return st;
+    const size_t need = sp_attn_workspace_bytes(0, L.total_tokens, n_groups, L.total_responses, n_q_heads, n_kv_heads,
+                                                head_dim, dtype);
+    if (!workspace || misaligned(workspace) || workspace_bytes < need)
+        return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
+                    workspace_bytes, need);
+    hipStream_t s = (hipStream_t)stream;
+    sp::Problem p{};
+    p.tab = (const int*)workspace;
+    p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
+    p.Hq = n_q_heads; p.Hkv = n_kv_heads; p.head_dim = head_dim; p.scale = softmax_scale;
+    p.host_group_tokens = L.group_tokens.data();
+    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    if (e == hipSuccess) {
+        if (dtype == SP_BF16) {
+            p.n_sets = n_sets;
+            for (int i = 0; i < n_sets; ++i) { p.qs[i] = q[i]; p.ks[i] = k[i]; p.vs[i] = v[i]; p.os[i] = o[i]; p.lses[i] = lse[i]; }
+            if (n_sets == 1) { p.q = q[0]; p.k = k[0]; p.v = v[0]; p.o_out = o[0]; p.lse_out = lse[0]; }
+            e = sp::launch_fwd_bf16(p, s);
+        } else {                 // the fp32 debug kernels take one set per launch
+            for (int i = 0; i < n_sets && e == hipSuccess; ++i) {
+                p.q = q[i]; p.k = k[i]; p.v = v[i]; p.o_out = o[i]; p.lse_out = lse[i];
+                e = sp::launch_fwd_f32(p, s);
+            }
+        }
+    }
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
+    return SP_OK;
+}
+
 const char* sp_attn_last_error(void) { return g_err; }
 const char* sp_attn_version(void) { return "0.1"; }
 

@@ -25,8 +25,10 @@ constexpr float P_LIMIT = 16384.0f;     // bound on a lane's per-tile sum of exp
 constexpr int TILE_BYTES = BN * 256;   // 64 rows x 128 bf16
 
 struct FwdArgs {
-    const __bf16* q; const __bf16* k; const __bf16* v;
-    __bf16* o; float* lse;
+    // one entry per tensor set; the sets share the packing, the schedule and the launch
+    const __bf16* q[MAX_SETS]; const __bf16* k[MAX_SETS]; const __bf16* v[MAX_SETS];
+    __bf16* o[MAX_SETS]; float* lse[MAX_SETS];
+    int blocks_per_set;
     const int* tab;
     int n_tiles, Hq, Hkv;
     float c;        // softmax_scale * log2(e)
@@ -51,8 +53,13 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     __shared__ __attribute__((aligned(1024))) char ldsKb[4][TILE_BYTES];      // K tile t lives in ldsKb[t & 3]
     __shared__ __attribute__((aligned(1024))) char ldsVb[4][TILE_BYTES];      // V tile t in ldsVb[t & 3]
 
+    // blocks are dealt set-major; blocks_per_set is a multiple of 8, so the block -> XCD mapping
+    // of a set does not depend on how many sets the launch carries
+    const int set = blockIdx.x / a.blocks_per_set;
+    const __bf16* const aq = a.q[set]; const __bf16* const ak = a.k[set]; const __bf16* const av = a.v[set];
+    __bf16* const ao = a.o[set]; float* const alse = a.lse[set];
     int tile, head;
-    if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
+    if (!decode_item(blockIdx.x - set * a.blocks_per_set, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
     int g, t0;
     find_tile(a.tab, tile, BM, g, t0);
     if (g < 0) return;
@@ -75,7 +82,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
     bf16x8 qreg[8];
     {
-        const __bf16* qp = a.q + ((int64_t)(gd.tok_base + (valid ? t : 0)) * a.Hq + head) * 128 + 8 * hh;
+        const __bf16* qp = aq + ((int64_t)(gd.tok_base + (valid ? t : 0)) * a.Hq + head) * 128 + 8 * hh;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             bf16x8 x = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
@@ -102,8 +109,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
     const int kvh = head / (a.Hq / a.Hkv);
     const int64_t kv_stride = (int64_t)a.Hkv * 128;
-    const __bf16* kbase = a.k + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
-    const __bf16* vbase = a.v + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
+    const __bf16* kbase = ak + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
+    const __bf16* vbase = av + ((int64_t)gd.tok_base * a.Hkv + kvh) * 128;
 
     // Tile copy global -> LDS.  The first wave of each SIMD (w < 4) is served first by the
     // instruction arbiter and reaches the workgroup barrier well ahead of its partner, so those
@@ -364,7 +371,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     const float lrt = pair_sum(lsr);
     if (valid) {
         const float inv = 1.0f / lrt;
-        __bf16* op = a.o + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
+        __bf16* op = ao + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -375,20 +382,27 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
                 *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * gq) = x;
             }
         if (hh == 0)
-            a.lse[(int64_t)head * T_total + gd.tok_base + t] = (m * cs + __log2f(ltot)) * LN2;
+            alse[(int64_t)head * T_total + gd.tok_base + t] = (m * cs + __log2f(ltot)) * LN2;
     }
 }
 
 }  // namespace
 
 hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
-    FwdArgs a;
-    a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v;
-    a.o = (__bf16*)p.o_out; a.lse = p.lse_out; a.tab = p.tab;
+    FwdArgs a{};
+    const int n_sets = p.n_sets > 1 ? p.n_sets : 1;
+    for (int i = 0; i < n_sets; ++i) {
+        const bool multi = p.n_sets > 1;
+        a.q[i] = (const __bf16*)(multi ? p.qs[i] : p.q); a.k[i] = (const __bf16*)(multi ? p.ks[i] : p.k);
+        a.v[i] = (const __bf16*)(multi ? p.vs[i] : p.v);
+        a.o[i] = (__bf16*)(multi ? p.os[i] : p.o_out); a.lse[i] = multi ? p.lses[i] : p.lse_out;
+    }
+    a.tab = p.tab;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive;
     a.n_tiles = count_tiles(p, 256);
-    const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
-    hipLaunchKernelGGL(fwd_kernel, dim3(grid), dim3(512), 0, s, a);
+    a.blocks_per_set = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
+    if (a.blocks_per_set % 8 != 0) a.blocks_per_set += 8 - a.blocks_per_set % 8;
+    hipLaunchKernelGGL(fwd_kernel, dim3(a.blocks_per_set * n_sets), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 

@@ -6,11 +6,17 @@
 namespace sp {
 
 constexpr unsigned STAGE_ROWSUM = 1u, STAGE_DKDV = 2u, STAGE_DQ = 4u;
+constexpr int MAX_SETS = 4;      // tensor sets that one forward launch can serve
 
 struct Problem {
     const void* q; const void* k; const void* v;
     const void* o; const float* lse; const void* d_o;     // backward inputs (o also fwd output)
     void* o_out; float* lse_out;                          // forward outputs
+    // forward over several tensor sets that share one packing (n_sets > 1): set i reads qs/ks/vs[i]
+    // and writes os/lses[i]; with n_sets <= 1 the single-set fields above are used
+    int n_sets;
+    const void* qs[MAX_SETS]; const void* ks[MAX_SETS]; const void* vs[MAX_SETS];
+    void* os[MAX_SETS]; float* lses[MAX_SETS];
     void* dq; void* dk; void* dv;                         // backward outputs
     const int* tab;                                       // segment table (device)
     float* Dbuf;                                          // [Hq, T_total] rowsum(dO*O) (device)

@@ -91,3 +91,25 @@ def test_config2_bf16_full():
 def test_naive_schedule_matches_oracle():
     w = W.Workload("naive", EDGE_GROUPS["ragged_multi"], 4, 2, 128, torch.bfloat16, 81, backward=False)
     check_full(w, backward=False, schedule=B.SP_SCHED_NAIVE_CAUSAL)
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_multi_set_forward_equals_separate_calls_and_oracle(dtype, d):
+    """Three (q, k, v) sets on one packing (policy / old policy / reference): one launch must
+    give bit for bit what three calls give, and each set must match the oracle."""
+    groups = [W.Group(333, [1, 63, 65, 0, 127, 129, 200]), W.Group(70, [300, 5]), W.Group(0, [40, 9])]
+    w = W.Workload("tri", groups, 6, 2, d, dtype, 91, backward=False, n_sets=3)
+    sets = [W.make_tensors(w, s) for s in range(3)]
+    qs, ks, vs = [dev(t.q) for t in sets], [dev(t.k) for t in sets], [dev(t.v) for t in sets]
+    os, lses = B.sp_attn_fwd_multi(qs, ks, vs, w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale)
+    torch.cuda.synchronize()
+    for s in range(3):
+        o1, lse1 = run_fwd(w, sets[s])
+        assert torch.equal(os[s], o1) and torch.equal(lses[s], lse1)
+        ro, rlse = oracle_fwd(w, sets[s])
+        gate(f"O[set {s}]", to64(os[s]), ro, dtype)
+        gate_lse(to64(lses[s]), rlse, dtype)
+    # one set through the same entry point
+    o0, l0 = B.sp_attn_fwd_multi(qs[:1], ks[:1], vs[:1], w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o0[0], os[0]) and torch.equal(l0[0], lses[0])

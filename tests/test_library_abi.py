@@ -72,3 +72,19 @@ def test_bad_stage_mask_is_rejected(lib):
         st = lib.sp_attn_bwd_batched_stages(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000,
                                             1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, stages, 0x1000, 1 << 20, None)
         assert st == B.SP_ERR_INVALID_ARG
+
+
+def test_multi_set_forward_rejects_bad_set_counts_and_arrays(lib):
+    one = (ctypes.c_int32 * 1)(4)
+    g = (ctypes.c_int32 * 1)(1)
+    r = (ctypes.c_int32 * 1)(3)
+    ptrs = (ctypes.c_void_p * 5)(*([0x1000] * 5))
+    def call(n, q=ptrs, ws=0x1000):
+        return lib.sp_attn_fwd_multi(n, q, ptrs, ptrs, ptrs, ptrs, 1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, ws,
+                                     1 << 20, None)
+    assert call(0) == B.SP_ERR_INVALID_ARG
+    assert call(5) == B.SP_ERR_INVALID_ARG
+    assert call(2, q=None) == B.SP_ERR_INVALID_ARG
+    bad = (ctypes.c_void_p * 5)(0x1000, 0x1008, 0x1000, 0x1000, 0x1000)
+    assert call(2, q=bad) == B.SP_ERR_INVALID_ARG           # set 1: misaligned q
+    assert call(3, ws=None) == B.SP_ERR_WORKSPACE
