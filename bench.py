@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--naive", action="store_true", help="also time the naive packed-causal forward")
+    ap.add_argument("--rope", action="store_true",
+                    help="also time the rotary-embedding pass (restarted positions) over q and k")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -218,6 +220,22 @@ def main():
         mms, sms = evm[0].elapsed_time(evm[1]) / 5, evm[1].elapsed_time(evm[2]) / 5
         out["multi_set_fwd"] = {"sets": w.n_sets, "one_launch_ms": round(mms, 4), "separate_launches_ms": round(sms, 4),
                                 "tflops": round(fwd_flops * w.n_sets / (mms * 1e-3) / 1e12, 2)}
+
+    if args.rope:
+        # HBM-bound pass: reads and writes q [T,Hq,d] and k [T,Hkv,d] once each
+        qr, kr = torch.empty_like(q), torch.empty_like(k)
+        evr = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        B.sp_attn_rope(q, pl, Gs, rl, 1e6, out=qr, workspace=ws)
+        evr[0].record()
+        for _ in range(10):
+            B.sp_attn_rope(q, pl, Gs, rl, 1e6, out=qr, workspace=ws)
+            B.sp_attn_rope(k, pl, Gs, rl, 1e6, out=kr, workspace=ws)
+        evr[1].record()
+        torch.cuda.synchronize()
+        rms = evr[0].elapsed_time(evr[1]) / 10
+        nbytes = 2 * (q.numel() + k.numel()) * q.element_size()
+        out["rope"] = {"ms": round(rms, 4), "bytes": nbytes, "bound": "hbm", "achieved": round(nbytes / (rms * 1e-3) / 1e9, 1),
+                       "peak": 8000.0, "unit": "GB/s", "frac": round(nbytes / (rms * 1e-3) / 8e12, 4)}
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

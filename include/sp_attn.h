@@ -166,6 +166,26 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
                             float softmax_scale, sp_dtype dtype,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* Rotary position embedding with the shared-prompt position indices (Section 4.3,
+ * modification 2): the prompt keeps positions 0 .. prompt_len-1 and EVERY response starts again
+ * at prompt_len, so attention over the pack equals per-sample training including positions.
+ * Half-split rotary form (the Qwen-family convention): theta_i = rope_base^(-2i/head_dim),
+ * pair (x[i], x[i + head_dim/2]) of a token at position p turns by the angle p * theta_i
+ * (angles are evaluated in double precision).
+ *   x, y          DEVICE [T_total, n_heads, head_dim], dtype elements; y may equal x (in place).
+ *                 Call it on q (n_q_heads) and on k (n_kv_heads) before sp_attn_fwd; v is not rotated.
+ *   inverse       0: rotate by +angle.  1: rotate by -angle, which turns the gradients that
+ *                 sp_attn_bwd returns for the rotated q / k into gradients for the unrotated ones.
+ *   packing       as sp_attn_fwd_batched.  head_dim 64 or 128 for either dtype.
+ *   workspace     DEVICE, at least sp_attn_workspace_bytes(0, T_total, n_groups, total_responses,
+ *                 n_heads, n_heads, head_dim, dtype) bytes (it holds the segment table).
+ * Asynchronous on `stream`; errors as sp_attn_fwd (SP_ERR_INVALID_ARG also for rope_base <= 1). */
+sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
+                       int32_t n_groups, const int32_t* prompt_lens,
+                       const int32_t* Gs, const int32_t* resp_lens_flat,
+                       int32_t head_dim, double rope_base, sp_dtype dtype,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* Text of the most recent error on the calling thread ("" if none).  The pointer
  * refers to thread-local static storage; the caller must not free it. */
 const char* sp_attn_last_error(void);

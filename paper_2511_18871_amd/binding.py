@@ -21,7 +21,7 @@ SP_SCHED_SHARED, SP_SCHED_NAIVE_CAUSAL = 0, 1
 SP_BWD_STAGE_ROWSUM, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2, 4, 7
 
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
-           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_last_error",
+           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_last_error",
            "sp_attn_version")
 
 _lib = None
@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     pp = ctypes.POINTER(ctypes.c_void_p)
     lib.sp_attn_fwd_multi.restype = ctypes.c_int
     lib.sp_attn_fwd_multi.argtypes = [i32, pp, pp, pp, pp, pp, i32, ip, ip, ip, i32, i32, i32, f32, ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_rope.restype = ctypes.c_int
+    lib.sp_attn_rope.argtypes = [vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
     lib.sp_attn_last_error.argtypes = []
     lib.sp_attn_version.restype = ctypes.c_char_p
@@ -171,6 +173,22 @@ def sp_attn_fwd_multi(qs, ks, vs, prompt_lens: Sequence[int], Gs: Sequence[int],
                                  _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
                                  _dtype_code(qs[0]), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return os, lses
+
+
+def sp_attn_rope(x, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int], rope_base: float,
+                 inverse: bool = False, out=None, workspace=None, stream=None):
+    """Rotary embedding of x [T, H, d] at the restarted position indices; returns the rotated tensor
+    (``out`` may be x itself)."""
+    lib = load_library()
+    T, H, d = x.shape
+    out = torch.empty_like(x) if out is None else out
+    if workspace is None:
+        need = workspace_bytes(False, T, len(prompt_lens), len(resp_lens_flat), H, H, d, _dtype_code(x))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    _check(lib.sp_attn_rope(x.data_ptr(), out.data_ptr(), H, int(inverse), len(prompt_lens), _i32(prompt_lens),
+                            _i32(Gs), _i32(resp_lens_flat), d, float(rope_base), _dtype_code(x),
+                            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out
 
 
 def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],

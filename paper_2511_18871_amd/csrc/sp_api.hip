@@ -253,6 +253,35 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
     return SP_OK;
 }
 
+sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse, int32_t n_groups,
+                       const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                       int32_t head_dim, double rope_base, sp_dtype dtype, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    g_err[0] = 0;
+    if (!x || !y) return fail(SP_ERR_INVALID_ARG, "a tensor pointer is NULL");
+    if (misaligned(x) || misaligned(y)) return fail(SP_ERR_INVALID_ARG, "tensor pointer is not 16-byte aligned");
+    if (n_heads < 1) return fail(SP_ERR_INVALID_ARG, "n_heads=%d", n_heads);
+    if (!(rope_base > 1.0) || !std::isfinite(rope_base))
+        return fail(SP_ERR_INVALID_ARG, "rope_base must be finite and > 1");
+    if (dtype != SP_BF16 && dtype != SP_F32) return fail(SP_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    if (head_dim != 64 && head_dim != 128) return fail(SP_ERR_UNSUPPORTED, "head_dim=%d (64 or 128)", head_dim);
+    Layout L;
+    sp_status st = build_table(n_groups, prompt_lens, Gs, resp_lens_flat, L);
+    if (st != SP_OK) return st;
+    const size_t need = sp_attn_workspace_bytes(0, L.total_tokens, n_groups, L.total_responses, n_heads, n_heads,
+                                                head_dim, dtype);
+    if (!workspace || misaligned(workspace) || workspace_bytes < need)
+        return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
+                    workspace_bytes, need);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    if (e == hipSuccess)
+        e = sp::launch_rope(x, y, (const int*)workspace, L.total_tokens, n_heads, head_dim, rope_base, inverse != 0,
+                            dtype == SP_F32, s);
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
+    return SP_OK;
+}
+
 const char* sp_attn_last_error(void) { return g_err; }
 const char* sp_attn_version(void) { return "0.1"; }
 

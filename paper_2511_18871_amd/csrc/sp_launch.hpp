@@ -36,6 +36,8 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s);
 hipError_t launch_fwd_f32(const Problem& p, hipStream_t s);
 hipError_t launch_bwd_f32(const Problem& p, hipStream_t s);
 hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s);
+hipError_t launch_rope(const void* x, void* y, const int* tab, int64_t total_tokens, int H, int d, double base,
+                       bool inverse, bool f32, hipStream_t s);
 hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s);
 
 inline int count_tiles(const Problem& p, int bm) {

@@ -88,3 +88,19 @@ def test_multi_set_forward_rejects_bad_set_counts_and_arrays(lib):
     bad = (ctypes.c_void_p * 5)(0x1000, 0x1008, 0x1000, 0x1000, 0x1000)
     assert call(2, q=bad) == B.SP_ERR_INVALID_ARG           # set 1: misaligned q
     assert call(3, ws=None) == B.SP_ERR_WORKSPACE
+
+
+def test_rope_rejects_bad_arguments(lib):
+    one = (ctypes.c_int32 * 1)(4)
+    g = (ctypes.c_int32 * 1)(1)
+    r = (ctypes.c_int32 * 1)(3)
+    def call(x=0x1000, y=0x1000, H=2, d=128, base=10000.0, dtype=B.SP_BF16, ws=0x1000):
+        return lib.sp_attn_rope(x, y, H, 0, 1, one, g, r, d, base, dtype, ws, 1 << 20, None)
+    assert call(x=None) == B.SP_ERR_INVALID_ARG
+    assert call(y=0x1002) == B.SP_ERR_INVALID_ARG
+    assert call(H=0) == B.SP_ERR_INVALID_ARG
+    assert call(base=1.0) == B.SP_ERR_INVALID_ARG
+    assert call(base=float("inf")) == B.SP_ERR_INVALID_ARG
+    assert call(d=96) == B.SP_ERR_UNSUPPORTED
+    assert call(dtype=5) == B.SP_ERR_UNSUPPORTED
+    assert call(ws=None) == B.SP_ERR_WORKSPACE
