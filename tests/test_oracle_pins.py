@@ -302,3 +302,37 @@ def test_batched_groups_are_independent():
         for a, b in zip(out[:4], one[:4]):
             np.testing.assert_array_equal(a[sl], b)
         base += n
+
+
+def test_micro_batches_sharing_a_prompt_accumulate_to_the_full_batch_gradient():
+    """The attention-level form of the paper's gradient identity (Section 3, Eq. 1: the gradient
+    of a group is the sum of its members' gradients): splitting the G responses of a prompt over
+    micro-batches, running only the RESPONSE rows of each pack [prompt | its responses] (upstream
+    gradient zero on the prompt rows) and the prompt rows once on their own, the dK/dV of the
+    prompt accumulate to the full-batch values and every response-row quantity is unchanged."""
+    rng = np.random.default_rng(11)
+    Lp, lens, Hq, Hkv, d = 6, [3, 2, 4, 1], 4, 2, 8
+    T = Lp + sum(lens)
+    q, k, v = rng.standard_normal((T, Hq, d)), rng.standard_normal((T, Hkv, d)), rng.standard_normal((T, Hkv, d))
+    d_o = rng.standard_normal((T, Hq, d))
+    scale = 0.4
+    dq, dk, dv, o, lse = orc.sp_attn_bwd(q, k, v, d_o, Lp, lens, scale)
+
+    starts = np.concatenate([[Lp], Lp + np.cumsum(lens)])
+    dk_p, dv_p = np.zeros((Lp, Hkv, d)), np.zeros((Lp, Hkv, d))
+    for members in ([0, 2], [1, 3]):                       # two micro-batches of two responses
+        idx = np.concatenate([np.arange(Lp)] + [np.arange(starts[i], starts[i + 1]) for i in members])
+        g = d_o[idx].copy()
+        g[:Lp] = 0.0                                       # response rows only
+        mdq, mdk, mdv, mo, mlse = orc.sp_attn_bwd(q[idx], k[idx], v[idx], g, Lp, [lens[i] for i in members], scale)
+        assert np.allclose(mo[Lp:], o[idx[Lp:]], atol=1e-13) and np.allclose(mlse[:, Lp:], lse[:, idx[Lp:]], atol=1e-13)
+        assert np.allclose(mdq[Lp:], dq[idx[Lp:]], atol=1e-12)
+        assert np.allclose(mdk[Lp:], dk[idx[Lp:]], atol=1e-12) and np.allclose(mdv[Lp:], dv[idx[Lp:]], atol=1e-12)
+        assert np.allclose(mdq[:Lp], 0.0)                  # zero upstream gradient: nothing flows to prompt queries
+        dk_p += mdk[:Lp]
+        dv_p += mdv[:Lp]
+    # the prompt rows, once: plain causal attention over the prompt with the prompt's upstream gradient
+    pdq, pdk, pdv, _, _ = orc.sp_attn_bwd(q[:Lp], k[:Lp], v[:Lp], d_o[:Lp], Lp, [], scale)
+    assert np.allclose(pdq, dq[:Lp], atol=1e-12)
+    assert np.allclose(dk_p + pdk, dk[:Lp], atol=1e-12)
+    assert np.allclose(dv_p + pdv, dv[:Lp], atol=1e-12)
