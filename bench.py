@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--naive", action="store_true", help="also time the naive packed-causal forward")
+    ap.add_argument("--response-rows", action="store_true",
+                    help="also time forward and backward restricted to response rows (a later micro-batch of a\n"
+                         "prompt whose prompt rows were already computed)")
     ap.add_argument("--rope", action="store_true",
                     help="also time the rotary-embedding pass (restarted positions) over q and k")
     ap.add_argument("--calib-copy", action="store_true",
@@ -220,6 +223,31 @@ def main():
         mms, sms = evm[0].elapsed_time(evm[1]) / 5, evm[1].elapsed_time(evm[2]) / 5
         out["multi_set_fwd"] = {"sets": w.n_sets, "one_launch_ms": round(mms, 4), "separate_launches_ms": round(sms, 4),
                                 "tflops": round(fwd_flops * w.n_sets / (mms * 1e-3) / 1e12, 2)}
+
+    if args.response_rows and do_bwd:
+        fl = B.SP_FLAG_RESPONSE_ROWS
+        evq = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        B.sp_attn_fwd_batched_ex(q, k, v, pl, Gs, rl, scale, fl, o=o, lse=lse, workspace=ws)
+        B.sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, pl, Gs, rl, scale, fl | B.SP_FLAG_ACCUMULATE_DKDV, dq=dq, dk=dk,
+                                 dv=dv, workspace=ws)
+        evq[0].record()
+        for _ in range(5):
+            B.sp_attn_fwd_batched_ex(q, k, v, pl, Gs, rl, scale, fl, o=o, lse=lse, workspace=ws)
+        evq[1].record()
+        for _ in range(5):
+            B.sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, pl, Gs, rl, scale, fl | B.SP_FLAG_ACCUMULATE_DKDV, dq=dq,
+                                     dk=dk, dv=dv, workspace=ws)
+        evq[2].record()
+        torch.cuda.synchronize()
+        # pairs whose query is a response row (terms B and C of the section's complexity split)
+        pairs_all = sum(W.allowed_pairs(g) for g in w.groups)
+        pairs_resp = pairs_all - sum(g.prompt_len * (g.prompt_len + 1) // 2 for g in w.groups)
+        fms, bms = evq[0].elapsed_time(evq[1]) / 5, evq[1].elapsed_time(evq[2]) / 5
+        rf = 4.0 * d * pairs_resp * Hq
+        out["response_rows"] = {"pair_fraction": round(pairs_resp / pairs_all, 4), "fwd_ms": round(fms, 4),
+                                "bwd_ms": round(bms, 4), "fwd_tflops": round(rf / (fms * 1e-3) / 1e12, 2),
+                                "bwd_tflops": round(2.5 * rf / (bms * 1e-3) / 1e12, 2)}
+        # the buffers were overwritten / accumulated into: restore nothing, the timed steps are done
 
     if args.rope:
         # HBM-bound pass: reads and writes q [T,Hq,d] and k [T,Hkv,d] once each

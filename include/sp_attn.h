@@ -144,6 +144,44 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
                                      float softmax_scale, sp_dtype dtype, uint32_t stages,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Micro-batches that share a prompt.  When the G responses of a prompt are spread over several
+ * micro-batches (the paper's runs share 16 of 32 rollouts per micro-batch), each micro-batch packs
+ * [prompt | its responses] and the gradient of the group is the sum over its members (Section 3,
+ * Eq. 1).  The prompt rows are then the same in every micro-batch, and two flags let a caller
+ * compute them once instead of once per micro-batch:
+ *   SP_FLAG_RESPONSE_ROWS     forward: o and lse are written for response rows only (prompt rows
+ *                             of the outputs keep their contents, e.g. those of the micro-batch
+ *                             that ran in full).  backward: dq is written for response rows only
+ *                             and only response rows contribute to dk, dv -- exactly the backward
+ *                             for an upstream gradient that is zero on the prompt rows, without
+ *                             visiting the prompt-by-prompt part of the mask.
+ *   SP_FLAG_ACCUMULATE_DKDV   backward: dk, dv are ADDED to what the buffers hold (read-modify-write
+ *                             in the output dtype) instead of overwritten, so the prompt's dk/dv
+ *                             can be summed over micro-batches in place (each accumulation
+ *                             rounds the running sum to the output dtype once more).
+ *                             With SP_FLAG_RESPONSE_ROWS the backward reads o and lse on response
+ *                             rows only; their prompt rows may hold anything.
+ * The prompt rows' own backward (plain causal attention over the prompt, with the upstream
+ * gradient of the prompt rows summed over the micro-batches) is an ordinary call with G = 0.
+ * The _ex entry points are sp_attn_fwd_batched / sp_attn_bwd_batched_stages with a flags word;
+ * flags = 0 gives those calls.  SP_ERR_INVALID_ARG for unknown bits, or ACCUMULATE on a forward. */
+#define SP_FLAG_RESPONSE_ROWS   1u
+#define SP_FLAG_ACCUMULATE_DKDV 2u
+sp_status sp_attn_fwd_batched_ex(const void* q, const void* k, const void* v, void* o, float* lse,
+                                 int32_t n_groups, const int32_t* prompt_lens,
+                                 const int32_t* Gs, const int32_t* resp_lens_flat,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                 float softmax_scale, sp_dtype dtype, sp_schedule schedule,
+                                 uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
+sp_status sp_attn_bwd_batched_ex(const void* q, const void* k, const void* v,
+                                 const void* o, const float* lse, const void* d_o,
+                                 void* dq, void* dk, void* dv,
+                                 int32_t n_groups, const int32_t* prompt_lens,
+                                 const int32_t* Gs, const int32_t* resp_lens_flat,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                 float softmax_scale, sp_dtype dtype, uint32_t stages,
+                                 uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Forward for several tensor sets that share ONE packing, in one launch: the policy, old-policy
  * and reference models of a GRPO step score the same packed sequences, so their three
  * attention forwards differ only in q, k, v (Section 3.2: all log-probabilities of a

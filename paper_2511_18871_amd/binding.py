@@ -19,9 +19,11 @@ SP_BF16, SP_F32 = 0, 1
 SP_SCHED_SHARED, SP_SCHED_NAIVE_CAUSAL = 0, 1
 
 SP_BWD_STAGE_ROWSUM, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2, 4, 7
+SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
-           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_last_error",
+           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
+           "sp_attn_last_error",
            "sp_attn_version")
 
 _lib = None
@@ -63,6 +65,12 @@ def load_library() -> ctypes.CDLL:
     pp = ctypes.POINTER(ctypes.c_void_p)
     lib.sp_attn_fwd_multi.restype = ctypes.c_int
     lib.sp_attn_fwd_multi.argtypes = [i32, pp, pp, pp, pp, pp, i32, ip, ip, ip, i32, i32, i32, f32, ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_fwd_batched_ex.restype = ctypes.c_int
+    lib.sp_attn_fwd_batched_ex.argtypes = [vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_uint32, vp, sz, vp]
+    lib.sp_attn_bwd_batched_ex.restype = ctypes.c_int
+    lib.sp_attn_bwd_batched_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32,
+                                           ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32, vp, sz, vp]
     lib.sp_attn_rope.restype = ctypes.c_int
     lib.sp_attn_rope.argtypes = [vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
@@ -173,6 +181,43 @@ def sp_attn_fwd_multi(qs, ks, vs, prompt_lens: Sequence[int], Gs: Sequence[int],
                                  _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
                                  _dtype_code(qs[0]), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return os, lses
+
+
+def sp_attn_fwd_batched_ex(q, k, v, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int],
+                           softmax_scale: float, flags: int, o=None, lse=None, workspace=None, stream=None,
+                           schedule: int = SP_SCHED_SHARED):
+    """sp_attn_fwd_batched with a flags word (SP_FLAG_RESPONSE_ROWS).  Rows that the flags exclude keep
+    whatever ``o`` / ``lse`` held."""
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty(Hq, T, dtype=torch.float32, device=q.device) if lse is None else lse
+    workspace = _workspace(False, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    _check(lib.sp_attn_fwd_batched_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                      len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d,
+                                      softmax_scale, _dtype_code(q), schedule, flags, workspace.data_ptr(),
+                                      workspace.numel(), _stream_ptr(stream)))
+    return o, lse
+
+
+def sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],
+                           resp_lens_flat: Sequence[int], softmax_scale: float, flags: int, dq=None, dk=None, dv=None,
+                           workspace=None, stream=None, stages: int = 7):
+    """sp_attn_bwd_batched with a flags word (SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV)."""
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    workspace = _workspace(True, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    _check(lib.sp_attn_bwd_batched_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                      d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), len(prompt_lens),
+                                      _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
+                                      _dtype_code(q), stages, flags, workspace.data_ptr(), workspace.numel(),
+                                      _stream_ptr(stream)))
+    return dq, dk, dv
 
 
 def sp_attn_rope(x, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int], rope_base: float,

@@ -95,8 +95,12 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
               const void* d_o, void* o_out, float* lse_out, void* dq, void* dk, void* dv,
               int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
               int32_t Hq, int32_t Hkv, int32_t d, float scale, sp_dtype dtype, sp_schedule schedule,
-              unsigned stages, void* workspace, size_t workspace_bytes, void* stream) {
+              unsigned stages, unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
     g_err[0] = 0;
+    if (flags & ~(unsigned)(SP_FLAG_RESPONSE_ROWS | SP_FLAG_ACCUMULATE_DKDV))
+        return fail(SP_ERR_INVALID_ARG, "unknown bits in flags=0x%x", flags);
+    if (!bwd && (flags & SP_FLAG_ACCUMULATE_DKDV))
+        return fail(SP_ERR_INVALID_ARG, "SP_FLAG_ACCUMULATE_DKDV is a backward flag");
     sp_status st = check_geometry(Hq, Hkv, d, scale, dtype);
     if (st != SP_OK) return st;
     if (schedule != SP_SCHED_SHARED && schedule != SP_SCHED_NAIVE_CAUSAL)
@@ -127,6 +131,8 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.Hq = Hq; p.Hkv = Hkv; p.head_dim = d; p.scale = scale;
     p.naive = schedule == SP_SCHED_NAIVE_CAUSAL;
     p.stages = stages;
+    p.resp_only = (flags & SP_FLAG_RESPONSE_ROWS) != 0;
+    p.accumulate = (flags & SP_FLAG_ACCUMULATE_DKDV) != 0;
     p.host_group_tokens = L.group_tokens.data();
 
     hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
@@ -156,7 +162,7 @@ sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, floa
                       int32_t head_dim, float softmax_scale, sp_dtype dtype, void* workspace,
                       size_t workspace_bytes, void* stream) {
     return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, 1, &prompt_len, &G,
-               resp_lens, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, workspace,
+               resp_lens, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, 0u, workspace,
                workspace_bytes, stream);
 }
 
@@ -165,7 +171,7 @@ sp_status sp_attn_bwd(const void* q, const void* k, const void* v, const void* o
                       int32_t G, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
                       sp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
     return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, 1, &prompt_len, &G, resp_lens, n_q_heads,
-               n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, workspace, workspace_bytes, stream);
+               n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, 0u, workspace, workspace_bytes, stream);
 }
 
 sp_status sp_attn_fwd_batched(const void* q, const void* k, const void* v, void* o, float* lse, int32_t n_groups,
@@ -174,7 +180,7 @@ sp_status sp_attn_fwd_batched(const void* q, const void* k, const void* v, void*
                               sp_dtype dtype, sp_schedule schedule, void* workspace, size_t workspace_bytes,
                               void* stream) {
     return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, n_groups, prompt_lens,
-               Gs, resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, schedule, SP_BWD_STAGE_ALL, workspace,
+               Gs, resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, schedule, SP_BWD_STAGE_ALL, 0u, workspace,
                workspace_bytes, stream);
 }
 
@@ -184,7 +190,7 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v, const
                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
                               sp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
     return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs, resp_lens_flat,
-               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, workspace, workspace_bytes,
+               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, SP_BWD_STAGE_ALL, 0u, workspace, workspace_bytes,
                stream);
 }
 
@@ -199,7 +205,31 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
     if (!(stages & SP_BWD_STAGE_DQ) && !dq) dq = const_cast<void*>(q);
     if (!(stages & SP_BWD_STAGE_DKDV)) { if (!dk) dk = const_cast<void*>(q); if (!dv) dv = const_cast<void*>(q); }
     return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs, resp_lens_flat,
-               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, stages, workspace,
+               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, stages, 0u, workspace,
+               workspace_bytes, stream);
+}
+
+sp_status sp_attn_fwd_batched_ex(const void* q, const void* k, const void* v, void* o, float* lse, int32_t n_groups,
+                                 const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                                 sp_dtype dtype, sp_schedule schedule, uint32_t flags, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, n_groups, prompt_lens,
+               Gs, resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, schedule, SP_BWD_STAGE_ALL,
+               flags, workspace, workspace_bytes, stream);
+}
+
+sp_status sp_attn_bwd_batched_ex(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                 const void* d_o, void* dq, void* dk, void* dv, int32_t n_groups,
+                                 const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                                 sp_dtype dtype, uint32_t stages, uint32_t flags, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (!(stages & SP_BWD_STAGE_ROWSUM) && !o) o = q;
+    if (!(stages & SP_BWD_STAGE_DQ) && !dq) dq = const_cast<void*>(q);
+    if (!(stages & SP_BWD_STAGE_DKDV)) { if (!dk) dk = const_cast<void*>(q); if (!dv) dv = const_cast<void*>(q); }
+    return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs, resp_lens_flat,
+               n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, stages, flags, workspace,
                workspace_bytes, stream);
 }
 

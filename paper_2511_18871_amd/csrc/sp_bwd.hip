@@ -29,6 +29,8 @@ struct BwdArgs {
     const int* tab;
     int n_tiles, Hq, Hkv;
     float scale, c;      // c = scale * log2(e)
+    int resp_only;       // only response rows are computed (dq) / contribute (dk, dv)
+    int accumulate;      // dk, dv are added to what the output buffers hold
 };
 
 // ------------------------------------------------------------------------------------
@@ -50,6 +52,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;
     const int64_t T_total = a.tab[1];
+    if (a.resp_only && t0 + BM <= Lp) return;      // a tile of prompt rows only
 
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
     const int c = l & 31, hh = l >> 5, j = l & 15, c16 = (l >> 4) & 1;
@@ -284,8 +287,9 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     // D = sum_s P dP equals rowsum(dO * O) exactly, but does not inherit the bf16 rounding of O.
     // Publish it for the dkdv pass (this workgroup owns these rows of D, so overwriting is safe).
     dsum = pair_sum(dsum);
-    if (valid && hh == 0) a.D[(int64_t)head * T_total + gd.tok_base + t] = dsum;
-    if (valid) {
+    const bool store = valid && !(a.resp_only && t < Lp);
+    if (store && hh == 0) a.D[(int64_t)head * T_total + gd.tok_base + t] = dsum;
+    if (store) {
         __bf16* op = a.dq + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -353,8 +357,11 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     // rows that see any key of the workgroup's tile
     const int s1 = min(s0 + BNK, Tg);
     const int row_end = s0 < Lp ? Tg : seg_end(gd, s1 - 1);
-    const int qt0 = s0 / BQ, qt1 = (row_end + BQ - 1) / BQ;
-    const int nqt = qt1 - qt0;
+    // with only response rows contributing, the rows start at the end of the prompt
+    const int row_lo = a.resp_only ? Lp : 0;
+    const int s_lo = max(s, row_lo);                   // first row that contributes to this lane's key
+    const int qt0 = max(s0, row_lo) / BQ, qt1 = (row_end + BQ - 1) / BQ;
+    const int nqt = max(qt1 - qt0, 0);
     const int rep = a.Hq / a.Hkv;
     const int total = nqt * rep;
     const int64_t q_stride = (int64_t)a.Hq * 128;
@@ -467,7 +474,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         qt = qt_n; hr = hr_n;
         if (++hr_n == rep) { hr_n = 0; --qt_n; }
         // no row of this wave's half sees any key of this wave
-        const bool skip = !wave_valid || r0 + 31 < ws0 || r0 >= e_max;
+        const bool skip = !wave_valid || r0 + 31 < max(ws0, row_lo) || r0 >= e_max;
         if (skip) continue;
 
         f32x16 sacc, pacc;
@@ -490,12 +497,12 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
             }
         }
         // every row of the half sees every key of the wave
-        const bool full = r0 >= ws1 && ws0 + 31 < Tg && r0 + 32 <= e_min;
+        const bool full = r0 >= max(ws1, row_lo) && ws0 + 31 < Tg && r0 + 32 <= e_min;
         if (!full) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int t = r0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-                sacc[r] = (t >= s && t < e_s) ? sacc[r] : -INFINITY;
+                sacc[r] = (t >= s_lo && t < e_s) ? sacc[r] : -INFINITY;
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -625,8 +632,10 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
                 for (int gq = 0; gq < 4; ++gq) {
                     const f32x4 y = *reinterpret_cast<const f32x4*>(xch + (db * 4 + gq) * 256);
                     bf16x4 x;
+                    bf16x4 old = {0, 0, 0, 0};
+                    if (a.accumulate) old = *reinterpret_cast<const bf16x4*>(out + orow + 32 * db + 8 * gq);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] = (__bf16)((acc[db][4 * gq + e] + y[e]) * mul);
+                    for (int e = 0; e < 4; ++e) x[e] = (__bf16)((acc[db][4 * gq + e] + y[e]) * mul + (float)old[e]);
                     *reinterpret_cast<bf16x4*>(out + orow + 32 * db + 8 * gq) = x;
                 }
         }
@@ -646,6 +655,7 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     a.lse = p.lse; a.D = p.Dbuf; a.L2 = p.Dbuf + (int64_t)p.Hq * p.total_tokens;
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;
     a.tab = p.tab; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
+    a.resp_only = p.resp_only; a.accumulate = p.accumulate;
     if (p.stages & STAGE_DQ) {
         constexpr int NWQ = 8;
         a.n_tiles = count_tiles(p, 32 * NWQ);

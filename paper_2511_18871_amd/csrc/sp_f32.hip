@@ -36,12 +36,25 @@ __global__ void upload_table_kernel(TabChunk chunk, int* __restrict__ dst, int o
 template <typename T>
 __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, const T* __restrict__ o,
                                                      const float* __restrict__ lse, float* __restrict__ D,
-                                                     int64_t T_total, int Hq, int dh) {
+                                                     int64_t T_total, int Hq, int dh,
+                                                     const int* __restrict__ tab, int resp_only) {
     const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int l = threadIdx.x & 63;
     if (gw >= T_total * Hq) return;
     const int64_t tok = gw / Hq;
     const int h = (int)(gw % Hq);
+    if (resp_only) {
+        // prompt rows take no part: their o / lse may hold anything, so they are not read, and the
+        // planes get finite placeholders (rows of a partly used tile are masked, not skipped)
+        const GroupDesc gd = load_group(tab, find_group(tab, (int)tok));
+        if ((int)tok - gd.tok_base < gd.Lp) {
+            if (l == 0) {
+                D[(int64_t)h * T_total + tok] = 0.f;
+                D[(int64_t)Hq * T_total + (int64_t)h * T_total + tok] = 0.f;
+            }
+            return;
+        }
+    }
     const T* a = d_o + gw * dh;
     const T* b = o + gw * dh;
     float acc = 0.f;
@@ -66,7 +79,7 @@ template <int DH>
 __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
                                                       const float* __restrict__ v, float* __restrict__ o,
                                                       float* __restrict__ lse, const int* __restrict__ tab,
-                                                      int Hq, int Hkv, float scale) {
+                                                      int Hq, int Hkv, float scale, int resp_only) {
     constexpr int PER = DH / 64;
     const int64_t T_total = tab[1];
     const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -75,6 +88,7 @@ __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ 
     const int tok = (int)(gw / Hq), h = (int)(gw % Hq);
     const GroupDesc gd = load_group(tab, find_group(tab, tok));
     const int t = tok - gd.tok_base;
+    if (resp_only && t < gd.Lp) return;
     const int st = seg_start(gd, t);
     const int kvh = h / (Hq / Hkv);
     const float* qrow = q + ((int64_t)tok * Hq + h) * DH;
@@ -118,7 +132,7 @@ __global__ __launch_bounds__(256) void bwd_dq_f32_kernel(const float* __restrict
                                                          const float* __restrict__ v, const float* __restrict__ d_o,
                                                          const float* __restrict__ lse, const float* __restrict__ D,
                                                          float* __restrict__ dq, const int* __restrict__ tab,
-                                                         int Hq, int Hkv, float scale) {
+                                                         int Hq, int Hkv, float scale, int resp_only) {
     constexpr int PER = DH / 64;
     const int64_t T_total = tab[1];
     const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -127,6 +141,7 @@ __global__ __launch_bounds__(256) void bwd_dq_f32_kernel(const float* __restrict
     const int tok = (int)(gw / Hq), h = (int)(gw % Hq);
     const GroupDesc gd = load_group(tab, find_group(tab, tok));
     const int t = tok - gd.tok_base;
+    if (resp_only && t < gd.Lp) return;
     const int st = seg_start(gd, t);
     const int kvh = h / (Hq / Hkv);
     const float* qrow = q + ((int64_t)tok * Hq + h) * DH;
@@ -170,7 +185,8 @@ __global__ __launch_bounds__(256) void bwd_dkdv_f32_kernel(const float* __restri
                                                            const float* __restrict__ v, const float* __restrict__ d_o,
                                                            const float* __restrict__ lse, const float* __restrict__ D,
                                                            float* __restrict__ dk, float* __restrict__ dv,
-                                                           const int* __restrict__ tab, int Hq, int Hkv, float scale) {
+                                                           const int* __restrict__ tab, int Hq, int Hkv, float scale,
+                                                           int resp_only, int accumulate) {
     constexpr int PER = DH / 64;
     const int64_t T_total = tab[1];
     const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -189,7 +205,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_f32_kernel(const float* __restri
     for (int e = 0; e < PER; ++e) { ak[e] = 0.f; av[e] = 0.f; }
     for (int hr = 0; hr < rep; ++hr) {
         const int h = kvh * rep + hr;
-        for (int r0 = s; r0 < row_end; r0 += 64) {
+        for (int r0 = resp_only ? max(s, gd.Lp) : s; r0 < row_end; r0 += 64) {
             const int t = r0 + l;
             float p = 0.f, ds = 0.f;
             if (t < row_end) {
@@ -213,7 +229,10 @@ __global__ __launch_bounds__(256) void bwd_dkdv_f32_kernel(const float* __restri
     float* okr = dk + ((int64_t)tok * Hkv + kvh) * DH;
     float* ovr = dv + ((int64_t)tok * Hkv + kvh) * DH;
 #pragma unroll
-    for (int e = 0; e < PER; ++e) { okr[l + 64 * e] = scale * ak[e]; ovr[l + 64 * e] = av[e]; }
+    for (int e = 0; e < PER; ++e) {
+        okr[l + 64 * e] = scale * ak[e] + (accumulate ? okr[l + 64 * e] : 0.f);
+        ovr[l + 64 * e] = av[e] + (accumulate ? ovr[l + 64 * e] : 0.f);
+    }
 }
 
 inline int blocks_for_waves(int64_t waves) { return (int)((waves + 3) / 4); }
@@ -237,10 +256,10 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
     const int grid = blocks_for_waves(p.total_tokens * p.Hq);
     if (f32)
         hipLaunchKernelGGL(rowsum_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)p.d_o,
-                           (const float*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
+                           (const float*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only);
     else
         hipLaunchKernelGGL(rowsum_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)p.d_o,
-                           (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim);
+                           (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only);
     return hipGetLastError();
 }
 
@@ -248,10 +267,10 @@ hipError_t launch_fwd_f32(const Problem& p, hipStream_t s) {
     const int grid = blocks_for_waves(p.total_tokens * p.Hq);
     if (p.head_dim == 64)
         hipLaunchKernelGGL(fwd_f32_kernel<64>, dim3(grid), dim3(256), 0, s, (const float*)p.q, (const float*)p.k,
-                           (const float*)p.v, (float*)p.o_out, p.lse_out, p.tab, p.Hq, p.Hkv, p.scale);
+                           (const float*)p.v, (float*)p.o_out, p.lse_out, p.tab, p.Hq, p.Hkv, p.scale, p.resp_only);
     else
         hipLaunchKernelGGL(fwd_f32_kernel<128>, dim3(grid), dim3(256), 0, s, (const float*)p.q, (const float*)p.k,
-                           (const float*)p.v, (float*)p.o_out, p.lse_out, p.tab, p.Hq, p.Hkv, p.scale);
+                           (const float*)p.v, (float*)p.o_out, p.lse_out, p.tab, p.Hq, p.Hkv, p.scale, p.resp_only);
     return hipGetLastError();
 }
 
@@ -266,11 +285,11 @@ hipError_t launch_bwd_f32(const Problem& p, hipStream_t s) {
     if (p.stages & STAGE_DQ)                                                                               \
     hipLaunchKernelGGL(bwd_dq_f32_kernel<DH>, dim3(gq), dim3(256), 0, s, (const float*)p.q, (const float*)p.k, \
                        (const float*)p.v, (const float*)p.d_o, p.lse, p.Dbuf, (float*)p.dq, p.tab, p.Hq,   \
-                       p.Hkv, p.scale);                                                                    \
+                       p.Hkv, p.scale, p.resp_only);                                                       \
     if (p.stages & STAGE_DKDV)                                                                             \
     hipLaunchKernelGGL(bwd_dkdv_f32_kernel<DH>, dim3(gk), dim3(256), 0, s, (const float*)p.q,              \
                        (const float*)p.k, (const float*)p.v, (const float*)p.d_o, p.lse, p.Dbuf,           \
-                       (float*)p.dk, (float*)p.dv, p.tab, p.Hq, p.Hkv, p.scale);
+                       (float*)p.dk, (float*)p.dv, p.tab, p.Hq, p.Hkv, p.scale, p.resp_only, p.accumulate);
     if (p.head_dim == 64) { SP_F32_BWD(64) } else { SP_F32_BWD(128) }
 #undef SP_F32_BWD
     return hipGetLastError();

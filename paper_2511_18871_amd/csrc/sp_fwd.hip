@@ -33,6 +33,7 @@ struct FwdArgs {
     int n_tiles, Hq, Hkv;
     float c;        // softmax_scale * log2(e)
     int naive;
+    int resp_only;  // compute and write response rows only
 };
 
 // ------------------------------------------------------------------------------------
@@ -66,6 +67,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;
     const int T_total = a.tab[1];
+    if (a.resp_only && t0 + BM <= Lp) return;      // a tile of prompt rows only
 
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
     const int c = l & 31, hh = l >> 5, j16 = l & 15, c16 = (l >> 4) & 1;
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // LSE uses the unrounded sum.
     const float ltot = pair_sum(lsum);
     const float lrt = pair_sum(lsr);
-    if (valid) {
+    if (valid && !(a.resp_only && t < Lp)) {
         const float inv = 1.0f / lrt;
         __bf16* op = ao + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
 #pragma unroll
@@ -398,7 +400,7 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
         a.o[i] = (__bf16*)(multi ? p.os[i] : p.o_out); a.lse[i] = multi ? p.lses[i] : p.lse_out;
     }
     a.tab = p.tab;
-    a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive;
+    a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive; a.resp_only = p.resp_only;
     a.n_tiles = count_tiles(p, 256);
     a.blocks_per_set = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
     if (a.blocks_per_set % 8 != 0) a.blocks_per_set += 8 - a.blocks_per_set % 8;

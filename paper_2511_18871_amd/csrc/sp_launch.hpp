@@ -27,6 +27,8 @@ struct Problem {
     float scale;
     int naive;                                            // forward: naive packed-causal schedule
     unsigned stages;                                      // backward: SP_BWD_STAGE_* bits to run
+    int resp_only;                                        // only response rows are computed / contribute
+    int accumulate;                                       // backward: dk, dv += instead of =
     // host copies of the per-group token counts, for grid sizing
     const int* host_group_tokens;
 };

@@ -104,3 +104,21 @@ def test_rope_rejects_bad_arguments(lib):
     assert call(d=96) == B.SP_ERR_UNSUPPORTED
     assert call(dtype=5) == B.SP_ERR_UNSUPPORTED
     assert call(ws=None) == B.SP_ERR_WORKSPACE
+
+
+def test_flags_word_is_validated(lib):
+    one = (ctypes.c_int32 * 1)(4)
+    g = (ctypes.c_int32 * 1)(1)
+    r = (ctypes.c_int32 * 1)(3)
+    P = 0x1000
+    def fwd(flags):
+        return lib.sp_attn_fwd_batched_ex(P, P, P, P, P, 1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, B.SP_SCHED_SHARED,
+                                          flags, None, 0, None)
+    def bwd(flags):
+        return lib.sp_attn_bwd_batched_ex(P, P, P, P, P, P, P, P, P, 1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, 7, flags,
+                                          None, 0, None)
+    assert fwd(4) == B.SP_ERR_INVALID_ARG and bwd(8) == B.SP_ERR_INVALID_ARG
+    assert fwd(B.SP_FLAG_ACCUMULATE_DKDV) == B.SP_ERR_INVALID_ARG
+    # valid flags pass the flag check and fail later, at the (missing) workspace
+    assert fwd(B.SP_FLAG_RESPONSE_ROWS) == B.SP_ERR_WORKSPACE
+    assert bwd(B.SP_FLAG_RESPONSE_ROWS | B.SP_FLAG_ACCUMULATE_DKDV) == B.SP_ERR_WORKSPACE
