@@ -204,21 +204,8 @@ __device__ __forceinline__ void async_copy16(const void* gptr, char* lds_base) {
                  :: "v"(gptr), "s"(lds_addr) : "memory");
 }
 // Same copy with the global address split into a wave-uniform 64-bit base (scalar registers)
-// and a 32-bit per-lane byte offset, so that a kernel can keep the lane part constant and
-// advance only the scalar base from tile to tile.
-__device__ __forceinline__ void async_copy16_so(const void* sbase, unsigned voff, char* lds_base) {
-    const unsigned lds_addr = __builtin_amdgcn_readfirstlane(
-        (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);
-    const uint64_t b = (uint64_t)(uintptr_t)sbase;
-    // readfirstlane returns a signed int: narrow to unsigned before widening, or the low
-    // half would be sign-extended into the high half
-    const uint64_t bs = ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
-                        (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(bs), "s"(lds_addr) : "memory");
-}
-// Same copy for callers that already hold the base as a 64-bit scalar and the LDS destination
-// as a byte address (both wave-uniform).
+// and a 32-bit per-lane byte offset, and the LDS destination given as a byte address: a kernel
+// keeps the lane part constant and advances only the scalar base from tile to tile.
 __device__ __forceinline__ void async_copy16_sm(uint64_t sbase, unsigned voff, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");

@@ -37,16 +37,16 @@ struct FwdArgs {
 };
 
 // ------------------------------------------------------------------------------------
-// Hand-scheduled software-pipelined forward.  Per key tile j a wave runs two blocks, each of
-// which mixes one MFMA stream with the vector-ALU work of a DIFFERENT tile:
-//   M(j): O^T += V(j-1)^T P(j-1)^T   (MFMA)   with   row max of S(j)            (VALU)
-//   E(j): S(j+1) = K(j+1) Q^T        (MFMA)   with   exp2 / row sum / bf16 P(j) (VALU)
-// The running-max update and the (rare) rescale of O sit between the two blocks.  Every block
-// is written as 16 sub-blocks of {LDS read for the MFMA two steps ahead, one MFMA, a slice
-// of the vector-ALU work}, fenced so the compiler keeps that order: an MFMA occupies the
-// SIMD's issue port for about half of its 32 cycles and hides four to five vector
-// instructions, which is what each slice holds.  V(j) and K(j+2) are copied into LDS during
-// step j, into the buffer halves that step j-1 read last.
+// Hand-scheduled software-pipelined forward.  Step j of a wave holds the MFMAs of two tiles and
+// the vector-ALU work of a third:
+//   O^T += V(j-1)^T P(j-1)^T  (16 MFMAs),  S(j+1) = K(j+1) Q^T  (16 MFMAs),
+//   P(j) = exp2(S(j) c - m c), its row sums and its bf16 packing  (32 scores per lane).
+// The step is written as 32 slices of {LDS operand read for the MFMA two slices ahead, one
+// MFMA, the vector work of one score}, fenced so the compiler keeps that order: while MFMAs
+// stream, a SIMD takes about five other vector instructions per MFMA for free, which is what a
+// slice holds.  So that the exponentials can be spread this evenly they are taken against the
+// reference point m the row had before the tile (see `step`).  Two steps run per workgroup
+// barrier; the K and V tiles of the following two steps are copied into LDS meanwhile.
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     constexpr int BM = 256;
@@ -79,7 +79,6 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     const int tw0 = t0 + 32 * w;
     const bool wave_valid = tw0 < Tg;
     const int tw1 = min(tw0 + 31, Tg - 1);
-    const int st_first = wave_valid ? __builtin_amdgcn_readfirstlane(seg_start(gd, tw0)) : 0;
     const int st_last = wave_valid ? __builtin_amdgcn_readfirstlane(seg_start(gd, tw1)) : 0;
 
     bf16x8 qreg[8];
