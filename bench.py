@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--naive", action="store_true", help="also time the naive packed-causal forward")
+    ap.add_argument("--inputs", choices=["random", "zeros"], default="random",
+                    help="zeros: run the same kernels on all-zero tensors (a power diagnostic: the instruction\n"
+                         "stream is identical, only operand toggling differs; not the metric)")
     ap.add_argument("--response-rows", action="store_true",
                     help="also time forward and backward restricted to response rows (a later micro-batch of a\n"
                          "prompt whose prompt rows were already computed)")
@@ -107,6 +110,9 @@ def main():
     dev = torch.device("cuda:0")
     q, k, v = t.q.to(dev), t.k.to(dev), t.v.to(dev)
     d_o = t.d_o.to(dev) if t.d_o is not None else None
+    if args.inputs == "zeros":
+        q, k, v = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+        d_o = torch.zeros_like(d_o) if d_o is not None else None
     pl, Gs, rl = w.prompt_lens(), w.Gs(), w.resp_lens_flat()
     scale = w.softmax_scale
     T, Hq, Hkv, d = w.total_tokens, w.n_q_heads, w.n_kv_heads, w.head_dim
@@ -161,7 +167,8 @@ def main():
         "metric": "shared-prompt attn fwd+bwd useful TFLOP/s and % bf16 MFMA peak, 1xMI355X",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32",
+        "data": "synthetic" if args.inputs == "random" else "all-zero tensors (power diagnostic, not the metric)",
         "config": {"workload": w.name, "groups": len(w.groups), "prompt_len": w.groups[0].prompt_len,
                    "G": len(w.groups[0].resp_lens), "total_tokens": T, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "passes": "fwd+bwd" if do_bwd else "fwd"},
