@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--response-rows", action="store_true",
                     help="also time forward and backward restricted to response rows (a later micro-batch of a\n"
                          "prompt whose prompt rows were already computed)")
+    ap.add_argument("--loss", action="store_true",
+                    help="also time the response-token log-probability forward/backward and the GRPO objective\n"
+                         "over logits [T, 151936] generated on the device")
     ap.add_argument("--rope", action="store_true",
                     help="also time the rotary-embedding pass (restarted positions) over q and k")
     ap.add_argument("--calib-copy", action="store_true",
@@ -255,6 +258,37 @@ def main():
                                 "bwd_ms": round(bms, 4), "fwd_tflops": round(rf / (fms * 1e-3) / 1e12, 2),
                                 "bwd_tflops": round(2.5 * rf / (bms * 1e-3) / 1e12, 2)}
         # the buffers were overwritten / accumulated into: restore nothing, the timed steps are done
+
+    if args.loss:
+        # HBM-bound passes over the response rows of logits [T, V] (V = the Qwen2.5 vocabulary)
+        V = 151936
+        gen = torch.Generator(device=dev).manual_seed(w.seed)
+        z = torch.randn(T, V, generator=gen, device=dev, dtype=torch.float32).mul_(2.0).to(torch.bfloat16)
+        yl = torch.randint(0, V, (T,), generator=gen, device=dev, dtype=torch.int32)
+        dz = torch.empty_like(z)
+        n_resp_tok = sum(rl)
+        adv = torch.randn(len(rl), generator=gen, device=dev)
+        logp, lsev = B.sp_attn_logprob_fwd(z, yl, pl, Gs, rl)
+        old_lp = logp + 0.1 * torch.randn(T, generator=gen, device=dev)
+        evl = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        evl[0].record()
+        for _ in range(5):
+            B.sp_attn_logprob_fwd(z, yl, pl, Gs, rl, logp=logp, lse=lsev)
+        evl[1].record()
+        for _ in range(5):
+            _, gl = B.sp_attn_grpo_loss(logp, old_lp, old_lp, adv, pl, Gs, rl)
+        evl[2].record()
+        for _ in range(5):
+            B.sp_attn_logprob_bwd(z, yl, lsev, gl, pl, Gs, rl, dlogits=dz)
+        evl[3].record()
+        torch.cuda.synchronize()
+        fms, gms, bms = (evl[i].elapsed_time(evl[i + 1]) / 5 for i in range(3))
+        fb, bb = n_resp_tok * V * 2, 2 * n_resp_tok * V * 2
+        out["loss"] = {"vocab": V, "response_tokens": n_resp_tok,
+                       "logprob_fwd": {"ms": round(fms, 4), "bytes": fb, "achieved": round(fb / (fms * 1e-3) / 1e9, 1)},
+                       "logprob_bwd": {"ms": round(bms, 4), "bytes": bb, "achieved": round(bb / (bms * 1e-3) / 1e9, 1)},
+                       "grpo_ms": round(gms, 4), "bound": "hbm", "peak": 8000.0, "unit": "GB/s"}
+        del z, dz
 
     if args.rope:
         # HBM-bound pass: reads and writes q [T,Hq,d] and k [T,Hkv,d] once each

@@ -224,6 +224,46 @@ sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
                        int32_t head_dim, double rope_base, sp_dtype dtype,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Response-token loss (Section 4.3, modification 4; Section 2 objective) ------------------
+ * The loss of the pack is a cross-entropy over its RESPONSE tokens; prompt rows are discarded.
+ * All three calls take the packing of sp_attn_fwd_batched and touch response rows only: prompt
+ * rows of every per-token tensor are neither read nor written.  Workspace (DEVICE): at least
+ * sp_attn_loss_workspace_bytes(T_total, n_groups, total_responses) bytes.  Asynchronous on
+ * `stream`; errors as sp_attn_fwd.
+ *
+ * sp_attn_logprob_fwd   logp[t] = logits[t, labels[t]] - log sum_v exp(logits[t, v]); also returns
+ *                       that log-sum-exp in lse[t] for the backward.  A label outside [0, vocab)
+ *                       gives logp = -inf without touching memory.
+ *     logits  DEVICE [T_total, vocab], dtype elements, row-major;  labels  DEVICE int32 [T_total]
+ *     (the target of each row; the next-token shift is the caller's);  logp, lse  DEVICE fp32 [T_total]
+ * sp_attn_logprob_bwd   dlogits[t, v] = g[t] * (1[v == labels[t]] - exp(logits[t, v] - lse[t]))
+ *     g  DEVICE fp32 [T_total] = dL/dlogp;  dlogits  DEVICE [T_total, vocab], dtype elements
+ *     (may not alias logits)
+ * sp_attn_grpo_loss     loss = -1/R sum_k (L_k - beta D_k) over the R non-empty responses, with one
+ *                       advantage A_k per response (adv: DEVICE fp32 [total_responses], responses in
+ *                       packing order over all groups), |o_k| its token count and, per token,
+ *                         r = exp(logp - logp_old),  L_k = 1/|o_k| sum min(r A_k, clip(r, 1-eps_low, 1+eps_high) A_k),
+ *                         u = logp_ref - logp,       D_k = 1/|o_k| sum (exp(u) - u - 1).
+ *                       The paper names these terms without printing them; this is the GRPO form.
+ *     logp, logp_old, logp_ref  DEVICE fp32 [T_total];  loss  DEVICE fp32 [1];
+ *     g  DEVICE fp32 [T_total] = dloss/dlogp (feeds sp_attn_logprob_bwd).  Bitwise repeatable. */
+size_t    sp_attn_loss_workspace_bytes(int64_t total_tokens, int32_t n_groups, int64_t total_responses);
+sp_status sp_attn_logprob_fwd(const void* logits, const int32_t* labels, float* logp, float* lse,
+                              int64_t vocab, int32_t n_groups, const int32_t* prompt_lens,
+                              const int32_t* Gs, const int32_t* resp_lens_flat, sp_dtype dtype,
+                              void* workspace, size_t workspace_bytes, void* stream);
+sp_status sp_attn_logprob_bwd(const void* logits, const int32_t* labels, const float* lse,
+                              const float* g, void* dlogits, int64_t vocab,
+                              int32_t n_groups, const int32_t* prompt_lens,
+                              const int32_t* Gs, const int32_t* resp_lens_flat, sp_dtype dtype,
+                              void* workspace, size_t workspace_bytes, void* stream);
+sp_status sp_attn_grpo_loss(const float* logp, const float* logp_old, const float* logp_ref,
+                            const float* adv, float eps_low, float eps_high, float beta,
+                            float* loss, float* g,
+                            int32_t n_groups, const int32_t* prompt_lens,
+                            const int32_t* Gs, const int32_t* resp_lens_flat,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Text of the most recent error on the calling thread ("" if none).  The pointer
  * refers to thread-local static storage; the caller must not free it. */
 const char* sp_attn_last_error(void);

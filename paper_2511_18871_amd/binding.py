@@ -23,8 +23,8 @@ SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
            "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
-           "sp_attn_last_error",
-           "sp_attn_version")
+           "sp_attn_loss_workspace_bytes", "sp_attn_logprob_fwd", "sp_attn_logprob_bwd", "sp_attn_grpo_loss",
+           "sp_attn_last_error", "sp_attn_version")
 
 _lib = None
 
@@ -71,6 +71,15 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_bwd_batched_ex.restype = ctypes.c_int
     lib.sp_attn_bwd_batched_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32,
                                            ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32, vp, sz, vp]
+    i64 = ctypes.c_int64
+    lib.sp_attn_loss_workspace_bytes.restype = sz
+    lib.sp_attn_loss_workspace_bytes.argtypes = [i64, i32, i64]
+    lib.sp_attn_logprob_fwd.restype = ctypes.c_int
+    lib.sp_attn_logprob_fwd.argtypes = [vp, vp, vp, vp, i64, i32, ip, ip, ip, ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_logprob_bwd.restype = ctypes.c_int
+    lib.sp_attn_logprob_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i32, ip, ip, ip, ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_grpo_loss.restype = ctypes.c_int
+    lib.sp_attn_grpo_loss.argtypes = [vp, vp, vp, vp, f32, f32, f32, vp, vp, i32, ip, ip, ip, vp, sz, vp]
     lib.sp_attn_rope.restype = ctypes.c_int
     lib.sp_attn_rope.argtypes = [vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
@@ -218,6 +227,57 @@ def sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs:
                                       _dtype_code(q), stages, flags, workspace.data_ptr(), workspace.numel(),
                                       _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def _loss_ws(T, n_groups, n_resp, device, workspace):
+    if workspace is None:
+        need = load_library().sp_attn_loss_workspace_bytes(T, n_groups, n_resp)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def sp_attn_logprob_fwd(logits, labels, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int],
+                        logp=None, lse=None, workspace=None, stream=None):
+    """Log-probability of labels[t] at every response row t of logits [T, V].  Returns (logp, lse);
+    prompt rows keep whatever the output tensors held (zeros when allocated here)."""
+    lib = load_library()
+    T, V = logits.shape
+    logp = torch.zeros(T, dtype=torch.float32, device=logits.device) if logp is None else logp
+    lse = torch.zeros(T, dtype=torch.float32, device=logits.device) if lse is None else lse
+    workspace = _loss_ws(T, len(prompt_lens), len(resp_lens_flat), logits.device, workspace)
+    _check(lib.sp_attn_logprob_fwd(logits.data_ptr(), labels.data_ptr(), logp.data_ptr(), lse.data_ptr(), V,
+                                   len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat),
+                                   _dtype_code(logits), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return logp, lse
+
+
+def sp_attn_logprob_bwd(logits, labels, lse, g, prompt_lens: Sequence[int], Gs: Sequence[int],
+                        resp_lens_flat: Sequence[int], dlogits=None, workspace=None, stream=None):
+    lib = load_library()
+    T, V = logits.shape
+    dlogits = torch.zeros_like(logits) if dlogits is None else dlogits
+    workspace = _loss_ws(T, len(prompt_lens), len(resp_lens_flat), logits.device, workspace)
+    _check(lib.sp_attn_logprob_bwd(logits.data_ptr(), labels.data_ptr(), lse.data_ptr(), g.data_ptr(),
+                                   dlogits.data_ptr(), V, len(prompt_lens), _i32(prompt_lens), _i32(Gs),
+                                   _i32(resp_lens_flat), _dtype_code(logits), workspace.data_ptr(), workspace.numel(),
+                                   _stream_ptr(stream)))
+    return dlogits
+
+
+def sp_attn_grpo_loss(logp, logp_old, logp_ref, adv, prompt_lens: Sequence[int], Gs: Sequence[int],
+                      resp_lens_flat: Sequence[int], eps_low: float = 0.2, eps_high: float = 0.2, beta: float = 0.02,
+                      g=None, workspace=None, stream=None):
+    """GRPO objective over the response rows.  Returns (loss [1], g [T] = dloss/dlogp)."""
+    lib = load_library()
+    T = logp.shape[0]
+    loss = torch.zeros(1, dtype=torch.float32, device=logp.device)
+    g = torch.zeros(T, dtype=torch.float32, device=logp.device) if g is None else g
+    workspace = _loss_ws(T, len(prompt_lens), len(resp_lens_flat), logp.device, workspace)
+    _check(lib.sp_attn_grpo_loss(logp.data_ptr(), logp_old.data_ptr(), logp_ref.data_ptr(), adv.data_ptr(), eps_low,
+                                 eps_high, beta, loss.data_ptr(), g.data_ptr(), len(prompt_lens), _i32(prompt_lens),
+                                 _i32(Gs), _i32(resp_lens_flat), workspace.data_ptr(), workspace.numel(),
+                                 _stream_ptr(stream)))
+    return loss, g
 
 
 def sp_attn_rope(x, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int], rope_base: float,

@@ -312,6 +312,83 @@ sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
     return SP_OK;
 }
 
+size_t sp_attn_loss_workspace_bytes(int64_t total_tokens, int32_t n_groups, int64_t total_responses) {
+    if (total_tokens < 1 || n_groups < 1 || total_responses < 0) return 0;
+    return align256(table_words(n_groups, total_responses) * 4) + align256((size_t)(total_responses + 1) * 4);
+}
+
+namespace {
+// shared front end of the three loss calls: packing -> table in the workspace
+sp_status loss_setup(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                     void* workspace, size_t workspace_bytes, hipStream_t s, Layout& L, float** scratch) {
+    sp_status st = build_table(n_groups, prompt_lens, Gs, resp_lens_flat, L);
+    if (st != SP_OK) return st;
+    const size_t need = sp_attn_loss_workspace_bytes(L.total_tokens, n_groups, L.total_responses);
+    if (!workspace || misaligned(workspace) || workspace_bytes < need)
+        return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
+                    workspace_bytes, need);
+    *scratch = (float*)((char*)workspace + align256(L.words.size() * 4));
+    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
+    return SP_OK;
+}
+}  // namespace
+
+sp_status sp_attn_logprob_fwd(const void* logits, const int32_t* labels, float* logp, float* lse, int64_t vocab,
+                              int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
+                              const int32_t* resp_lens_flat, sp_dtype dtype, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    g_err[0] = 0;
+    if (!logits || !labels || !logp || !lse) return fail(SP_ERR_INVALID_ARG, "a pointer is NULL");
+    if (misaligned(logits)) return fail(SP_ERR_INVALID_ARG, "logits pointer is not 16-byte aligned");
+    if (vocab < 1) return fail(SP_ERR_INVALID_ARG, "vocab=%lld", (long long)vocab);
+    if (dtype != SP_BF16 && dtype != SP_F32) return fail(SP_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    Layout L; float* scratch = nullptr;
+    sp_status st = loss_setup(n_groups, prompt_lens, Gs, resp_lens_flat, workspace, workspace_bytes, (hipStream_t)stream, L, &scratch);
+    if (st != SP_OK) return st;
+    hipError_t e = sp::launch_logprob_fwd(logits, labels, logp, lse, (const int*)workspace, L.total_tokens, vocab,
+                                          dtype == SP_F32, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
+    return SP_OK;
+}
+
+sp_status sp_attn_logprob_bwd(const void* logits, const int32_t* labels, const float* lse, const float* g,
+                              void* dlogits, int64_t vocab, int32_t n_groups, const int32_t* prompt_lens,
+                              const int32_t* Gs, const int32_t* resp_lens_flat, sp_dtype dtype, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    if (!logits || !labels || !lse || !g || !dlogits) return fail(SP_ERR_INVALID_ARG, "a pointer is NULL");
+    if (misaligned(logits) || misaligned(dlogits)) return fail(SP_ERR_INVALID_ARG, "tensor pointer is not 16-byte aligned");
+    if (vocab < 1) return fail(SP_ERR_INVALID_ARG, "vocab=%lld", (long long)vocab);
+    if (dtype != SP_BF16 && dtype != SP_F32) return fail(SP_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
+    Layout L; float* scratch = nullptr;
+    sp_status st = loss_setup(n_groups, prompt_lens, Gs, resp_lens_flat, workspace, workspace_bytes, (hipStream_t)stream, L, &scratch);
+    if (st != SP_OK) return st;
+    hipError_t e = sp::launch_logprob_bwd(logits, labels, lse, g, dlogits, (const int*)workspace, L.total_tokens, vocab,
+                                          dtype == SP_F32, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
+    return SP_OK;
+}
+
+sp_status sp_attn_grpo_loss(const float* logp, const float* logp_old, const float* logp_ref, const float* adv,
+                            float eps_low, float eps_high, float beta, float* loss, float* g, int32_t n_groups,
+                            const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    if (!logp || !logp_old || !logp_ref || !adv || !loss || !g) return fail(SP_ERR_INVALID_ARG, "a pointer is NULL");
+    if (!(eps_low >= 0.f && eps_low < 1.f) || !(eps_high >= 0.f) || !std::isfinite(eps_high) || !std::isfinite(beta))
+        return fail(SP_ERR_INVALID_ARG, "eps_low must lie in [0, 1), eps_high in [0, inf), beta finite");
+    Layout L; float* scratch = nullptr;
+    sp_status st = loss_setup(n_groups, prompt_lens, Gs, resp_lens_flat, workspace, workspace_bytes, (hipStream_t)stream, L, &scratch);
+    if (st != SP_OK) return st;
+    int nonempty = 0;
+    for (int64_t r = 0; r < L.total_responses; ++r) nonempty += resp_lens_flat[r] > 0;
+    hipError_t e = sp::launch_grpo(logp, logp_old, logp_ref, adv, g, scratch, loss, (const int*)workspace,
+                                   (int)L.total_responses, nonempty, eps_low, eps_high, beta, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
+    return SP_OK;
+}
+
 const char* sp_attn_last_error(void) { return g_err; }
 const char* sp_attn_version(void) { return "0.1"; }
 

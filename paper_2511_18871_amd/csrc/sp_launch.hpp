@@ -40,6 +40,13 @@ hipError_t launch_bwd_f32(const Problem& p, hipStream_t s);
 hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s);
 hipError_t launch_rope(const void* x, void* y, const int* tab, int64_t total_tokens, int H, int d, double base,
                        bool inverse, bool f32, hipStream_t s);
+hipError_t launch_logprob_fwd(const void* z, const int* y, float* logp, float* lse, const int* tab,
+                              int64_t total_tokens, int64_t V, bool f32, hipStream_t s);
+hipError_t launch_logprob_bwd(const void* z, const int* y, const float* lse, const float* g, void* dz,
+                              const int* tab, int64_t total_tokens, int64_t V, bool f32, hipStream_t s);
+hipError_t launch_grpo(const float* logp, const float* old, const float* ref, const float* adv, float* g,
+                       float* J, float* loss, const int* tab, int n_resp, int n_nonempty, float eps_low,
+                       float eps_high, float beta, hipStream_t s);
 hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s);
 
 inline int count_tiles(const Problem& p, int bm) {

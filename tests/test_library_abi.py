@@ -122,3 +122,27 @@ def test_flags_word_is_validated(lib):
     # valid flags pass the flag check and fail later, at the (missing) workspace
     assert fwd(B.SP_FLAG_RESPONSE_ROWS) == B.SP_ERR_WORKSPACE
     assert bwd(B.SP_FLAG_RESPONSE_ROWS | B.SP_FLAG_ACCUMULATE_DKDV) == B.SP_ERR_WORKSPACE
+
+
+def test_loss_calls_reject_bad_arguments(lib):
+    one = (ctypes.c_int32 * 1)(4)
+    g = (ctypes.c_int32 * 1)(1)
+    r = (ctypes.c_int32 * 1)(3)
+    P = 0x1000
+    assert lib.sp_attn_loss_workspace_bytes(7, 1, 1) >= (4 + 6 + 1 + 1) * 4 + 8
+    assert lib.sp_attn_loss_workspace_bytes(0, 1, 1) == 0
+    f = lambda **kw: lib.sp_attn_logprob_fwd(kw.get("z", P), P, P, P, kw.get("V", 100), 1, one, g, r,
+                                             kw.get("dtype", B.SP_BF16), kw.get("ws", P), 1 << 20, None)
+    assert f(z=None) == B.SP_ERR_INVALID_ARG and f(z=0x1002) == B.SP_ERR_INVALID_ARG
+    assert f(V=0) == B.SP_ERR_INVALID_ARG
+    assert f(dtype=9) == B.SP_ERR_UNSUPPORTED
+    assert f(ws=None) == B.SP_ERR_WORKSPACE
+    b = lambda **kw: lib.sp_attn_logprob_bwd(P, P, P, P, kw.get("dz", P), 100, 1, one, g, r, B.SP_F32, kw.get("ws", P),
+                                             1 << 20, None)
+    assert b(dz=None) == B.SP_ERR_INVALID_ARG and b(ws=None) == B.SP_ERR_WORKSPACE
+    q = lambda **kw: lib.sp_attn_grpo_loss(P, P, P, kw.get("adv", P), kw.get("el", 0.2), kw.get("eh", 0.2),
+                                           kw.get("beta", 0.02), P, P, 1, one, g, r, kw.get("ws", P), 1 << 20, None)
+    assert q(adv=None) == B.SP_ERR_INVALID_ARG
+    assert q(el=1.0) == B.SP_ERR_INVALID_ARG and q(el=-0.1) == B.SP_ERR_INVALID_ARG
+    assert q(eh=float("inf")) == B.SP_ERR_INVALID_ARG and q(beta=float("nan")) == B.SP_ERR_INVALID_ARG
+    assert q(ws=None) == B.SP_ERR_WORKSPACE
