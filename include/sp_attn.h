@@ -163,8 +163,14 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
  *                             rows only; their prompt rows may hold anything.
  * The prompt rows' own backward (plain causal attention over the prompt, with the upstream
  * gradient of the prompt rows summed over the micro-batches) is an ordinary call with G = 0.
- * The _ex entry points are sp_attn_fwd_batched / sp_attn_bwd_batched_stages with a flags word;
- * flags = 0 gives those calls.  SP_ERR_INVALID_ARG for unknown bits, or ACCUMULATE on a forward. */
+ * The _ex entry points are sp_attn_fwd_batched / sp_attn_bwd_batched_stages with a flags word and
+ * one optional tensor; flags = 0 and o_lo = NULL give those calls.  SP_ERR_INVALID_ARG for unknown
+ * bits, or ACCUMULATE on a forward.
+ *   o_lo   DEVICE [T_total, n_q_heads, head_dim] bf16, or NULL.  The backward starts from
+ *          D = rowsum(d_o * o), and o is stored rounded to bf16; in rows dominated by one key that
+ *          rounding is the largest error of dq.  When the forward is given o_lo it also stores
+ *          what the rounding dropped (o_fp32 - o, itself rounded to bf16); handing the same buffer
+ *          to the backward makes D use o + o_lo.  bf16 only (SP_ERR_UNSUPPORTED with SP_F32). */
 #define SP_FLAG_RESPONSE_ROWS   1u
 #define SP_FLAG_ACCUMULATE_DKDV 2u
 sp_status sp_attn_fwd_batched_ex(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -172,7 +178,8 @@ sp_status sp_attn_fwd_batched_ex(const void* q, const void* k, const void* v, vo
                                  const int32_t* Gs, const int32_t* resp_lens_flat,
                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                  float softmax_scale, sp_dtype dtype, sp_schedule schedule,
-                                 uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
+                                 uint32_t flags, void* o_lo,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 sp_status sp_attn_bwd_batched_ex(const void* q, const void* k, const void* v,
                                  const void* o, const float* lse, const void* d_o,
                                  void* dq, void* dk, void* dv,
@@ -180,7 +187,8 @@ sp_status sp_attn_bwd_batched_ex(const void* q, const void* k, const void* v,
                                  const int32_t* Gs, const int32_t* resp_lens_flat,
                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                  float softmax_scale, sp_dtype dtype, uint32_t stages,
-                                 uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
+                                 uint32_t flags, const void* o_lo,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* Forward for several tensor sets that share ONE packing, in one launch: the policy, old-policy
  * and reference models of a GRPO step score the same packed sequences, so their three

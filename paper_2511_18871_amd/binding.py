@@ -67,10 +67,10 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_fwd_multi.argtypes = [i32, pp, pp, pp, pp, pp, i32, ip, ip, ip, i32, i32, i32, f32, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_fwd_batched_ex.restype = ctypes.c_int
     lib.sp_attn_fwd_batched_ex.argtypes = [vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32, ctypes.c_int,
-                                           ctypes.c_int, ctypes.c_uint32, vp, sz, vp]
+                                           ctypes.c_int, ctypes.c_uint32, vp, vp, sz, vp]
     lib.sp_attn_bwd_batched_ex.restype = ctypes.c_int
     lib.sp_attn_bwd_batched_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32,
-                                           ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32, vp, sz, vp]
+                                           ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32, vp, vp, sz, vp]
     i64 = ctypes.c_int64
     lib.sp_attn_loss_workspace_bytes.restype = sz
     lib.sp_attn_loss_workspace_bytes.argtypes = [i64, i32, i64]
@@ -194,7 +194,7 @@ def sp_attn_fwd_multi(qs, ks, vs, prompt_lens: Sequence[int], Gs: Sequence[int],
 
 def sp_attn_fwd_batched_ex(q, k, v, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int],
                            softmax_scale: float, flags: int, o=None, lse=None, workspace=None, stream=None,
-                           schedule: int = SP_SCHED_SHARED):
+                           schedule: int = SP_SCHED_SHARED, o_lo=None):
     """sp_attn_fwd_batched with a flags word (SP_FLAG_RESPONSE_ROWS).  Rows that the flags exclude keep
     whatever ``o`` / ``lse`` held."""
     lib = load_library()
@@ -205,14 +205,15 @@ def sp_attn_fwd_batched_ex(q, k, v, prompt_lens: Sequence[int], Gs: Sequence[int
     workspace = _workspace(False, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
     _check(lib.sp_attn_fwd_batched_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                       len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d,
-                                      softmax_scale, _dtype_code(q), schedule, flags, workspace.data_ptr(),
+                                      softmax_scale, _dtype_code(q), schedule, flags,
+                                      None if o_lo is None else o_lo.data_ptr(), workspace.data_ptr(),
                                       workspace.numel(), _stream_ptr(stream)))
     return o, lse
 
 
 def sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],
                            resp_lens_flat: Sequence[int], softmax_scale: float, flags: int, dq=None, dk=None, dv=None,
-                           workspace=None, stream=None, stages: int = 7):
+                           workspace=None, stream=None, stages: int = 7, o_lo=None):
     """sp_attn_bwd_batched with a flags word (SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV)."""
     lib = load_library()
     T, Hq, d = q.shape
@@ -224,8 +225,8 @@ def sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs:
     _check(lib.sp_attn_bwd_batched_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                       d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), len(prompt_lens),
                                       _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
-                                      _dtype_code(q), stages, flags, workspace.data_ptr(), workspace.numel(),
-                                      _stream_ptr(stream)))
+                                      _dtype_code(q), stages, flags, None if o_lo is None else o_lo.data_ptr(),
+                                      workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk, dv
 
 

@@ -95,8 +95,11 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
               const void* d_o, void* o_out, float* lse_out, void* dq, void* dk, void* dv,
               int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
               int32_t Hq, int32_t Hkv, int32_t d, float scale, sp_dtype dtype, sp_schedule schedule,
-              unsigned stages, unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
+              unsigned stages, unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
+              void* o_lo = nullptr) {
     g_err[0] = 0;
+    if (o_lo && misaligned(o_lo)) return fail(SP_ERR_INVALID_ARG, "o_lo pointer %p is not 16-byte aligned", o_lo);
+    if (o_lo && dtype != SP_BF16) return fail(SP_ERR_UNSUPPORTED, "o_lo is a bf16 option (fp32 outputs are not rounded)");
     if (flags & ~(unsigned)(SP_FLAG_RESPONSE_ROWS | SP_FLAG_ACCUMULATE_DKDV))
         return fail(SP_ERR_INVALID_ARG, "unknown bits in flags=0x%x", flags);
     if (!bwd && (flags & SP_FLAG_ACCUMULATE_DKDV))
@@ -132,6 +135,8 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.naive = schedule == SP_SCHED_NAIVE_CAUSAL;
     p.stages = stages;
     p.resp_only = (flags & SP_FLAG_RESPONSE_ROWS) != 0;
+    p.o_lo_out = bwd ? nullptr : o_lo;
+    p.o_lo = bwd ? o_lo : nullptr;
     p.accumulate = (flags & SP_FLAG_ACCUMULATE_DKDV) != 0;
     p.host_group_tokens = L.group_tokens.data();
 
@@ -212,25 +217,25 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
 sp_status sp_attn_fwd_batched_ex(const void* q, const void* k, const void* v, void* o, float* lse, int32_t n_groups,
                                  const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
-                                 sp_dtype dtype, sp_schedule schedule, uint32_t flags, void* workspace,
+                                 sp_dtype dtype, sp_schedule schedule, uint32_t flags, void* o_lo, void* workspace,
                                  size_t workspace_bytes, void* stream) {
     return run(false, q, k, v, nullptr, nullptr, nullptr, o, lse, nullptr, nullptr, nullptr, n_groups, prompt_lens,
                Gs, resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, schedule, SP_BWD_STAGE_ALL,
-               flags, workspace, workspace_bytes, stream);
+               flags, workspace, workspace_bytes, stream, o_lo);
 }
 
 sp_status sp_attn_bwd_batched_ex(const void* q, const void* k, const void* v, const void* o, const float* lse,
                                  const void* d_o, void* dq, void* dk, void* dv, int32_t n_groups,
                                  const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
-                                 sp_dtype dtype, uint32_t stages, uint32_t flags, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
+                                 sp_dtype dtype, uint32_t stages, uint32_t flags, const void* o_lo,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
     if (!(stages & SP_BWD_STAGE_ROWSUM) && !o) o = q;
     if (!(stages & SP_BWD_STAGE_DQ) && !dq) dq = const_cast<void*>(q);
     if (!(stages & SP_BWD_STAGE_DKDV)) { if (!dk) dk = const_cast<void*>(q); if (!dv) dv = const_cast<void*>(q); }
     return run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs, resp_lens_flat,
                n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED, stages, flags, workspace,
-               workspace_bytes, stream);
+               workspace_bytes, stream, const_cast<void*>(o_lo));
 }
 
 sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* const* k, const void* const* v,

@@ -37,7 +37,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, const T* __restrict__ o,
                                                      const float* __restrict__ lse, float* __restrict__ D,
                                                      int64_t T_total, int Hq, int dh,
-                                                     const int* __restrict__ tab, int resp_only) {
+                                                     const int* __restrict__ tab, int resp_only,
+                                                     const T* __restrict__ o_lo) {
     const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int l = threadIdx.x & 63;
     if (gw >= T_total * Hq) return;
@@ -58,7 +59,12 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, 
     const T* a = d_o + gw * dh;
     const T* b = o + gw * dh;
     float acc = 0.f;
-    for (int i = l; i < dh; i += 64) acc += (float)a[i] * (float)b[i];
+    if (o_lo) {          // o was stored with its rounding residual: D from the unrounded value
+        const T* c = o_lo + gw * dh;
+        for (int i = l; i < dh; i += 64) acc += (float)a[i] * ((float)b[i] + (float)c[i]);
+    } else {
+        for (int i = l; i < dh; i += 64) acc += (float)a[i] * (float)b[i];
+    }
     acc = wave_sum(acc);
     if (l == 0) {
         D[(int64_t)h * T_total + tok] = acc;
@@ -256,10 +262,10 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
     const int grid = blocks_for_waves(p.total_tokens * p.Hq);
     if (f32)
         hipLaunchKernelGGL(rowsum_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)p.d_o,
-                           (const float*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only);
+                           (const float*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only, (const float*)nullptr);
     else
         hipLaunchKernelGGL(rowsum_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)p.d_o,
-                           (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only);
+                           (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only, (const __bf16*)p.o_lo);
     return hipGetLastError();
 }
 

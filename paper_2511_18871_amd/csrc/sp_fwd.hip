@@ -34,6 +34,7 @@ struct FwdArgs {
     float c;        // softmax_scale * log2(e)
     int naive;
     int resp_only;  // compute and write response rows only
+    __bf16* o_lo;   // optional (single-set launches): o_fp32 - bf16(o), rounded to bf16, same layout as o
 };
 
 // ------------------------------------------------------------------------------------
@@ -381,6 +382,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) x[e] = (__bf16)(oacc[db][4 * gq + e] * inv);
                 *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * gq) = x;
+                if (a.o_lo) {        // what the rounding of o dropped: lets the backward form D from an unrounded o
+                    bf16x4 r;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) r[e] = (__bf16)(oacc[db][4 * gq + e] * inv - (float)x[e]);
+                    *reinterpret_cast<bf16x4*>(a.o_lo + (op - ao) + 32 * db + 8 * gq) = r;
+                }
             }
         if (hh == 0)
             alse[(int64_t)head * T_total + gd.tok_base + t] = (m * cs + __log2f(ltot)) * LN2;
@@ -400,6 +407,7 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
     }
     a.tab = p.tab;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive; a.resp_only = p.resp_only;
+    a.o_lo = n_sets == 1 ? (__bf16*)p.o_lo_out : nullptr;
     a.n_tiles = count_tiles(p, 256);
     a.blocks_per_set = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
     if (a.blocks_per_set % 8 != 0) a.blocks_per_set += 8 - a.blocks_per_set % 8;

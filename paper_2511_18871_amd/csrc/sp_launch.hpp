@@ -28,6 +28,8 @@ struct Problem {
     int naive;                                            // forward: naive packed-causal schedule
     unsigned stages;                                      // backward: SP_BWD_STAGE_* bits to run
     int resp_only;                                        // only response rows are computed / contribute
+    void* o_lo_out;                                       // forward (bf16): optional rounding residual of o
+    const void* o_lo;                                     // backward (bf16): optional residual for D
     int accumulate;                                       // backward: dk, dv += instead of =
     // host copies of the per-group token counts, for grid sizing
     const int* host_group_tokens;

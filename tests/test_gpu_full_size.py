@@ -100,3 +100,29 @@ def test_config5_extreme_sharing_large_logits():
     assert len(t.stressed_rows) > 100          # about 1 % of the K rows carry the x8 scale
     got = run_gpu(w, t, True)
     check_sampled(w, t, got, True, groups=(0,), n_rows=40, heads=[0, 17, 39], kv_check=(0, 3))
+
+
+def test_config5_residual_of_o_tightens_dq():
+    """With the rounding residual of o handed from forward to backward, D = rowsum(dO * o) no longer
+    carries o's bf16 rounding, which is the largest error of dq on this workload."""
+    w = W.config(5)
+    t = W.make_tensors(w)
+    q, k, v, d_o = t.q.cuda(), t.k.cuda(), t.v.cuda(), t.d_o.cuda()
+    pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
+    o_lo = torch.empty_like(q)
+    o, lse = B.sp_attn_fwd_batched_ex(q, k, v, pl, Gs, rl, sc, 0, o_lo=o_lo)
+    o_plain, lse_plain = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, sc)
+    assert torch.equal(o, o_plain) and torch.equal(lse, lse_plain)          # the option does not change o
+    dq, dk, dv = B.sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, pl, Gs, rl, sc, 0, o_lo=o_lo)
+    dq0, _, _ = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc)
+    torch.cuda.synchronize()
+    g = w.groups[0]
+    rng = np.random.default_rng(123)
+    rows = sample_rows(g, rng, 40)
+    heads = [0, 17, 39]
+    rdq = orc.sp_attn_bwd_rows(t.q, t.k, t.v, t.d_o, g.prompt_len, g.resp_lens, sc, rows, heads)
+    print(gate("dQ[with o_lo]", to64(dq.cpu())[rows][:, heads], rdq, w.dtype))
+    rms = lambda x: float(np.sqrt(np.mean((to64(x.cpu())[rows][:, heads] - rdq) ** 2)))
+    assert rms(dq) <= 0.7 * rms(dq0), (rms(dq), rms(dq0))
+    # the residual itself: o + o_lo is o's unrounded value to ~2^-17
+    assert float((o_lo.float().abs() <= 2.0 ** -8 * o.float().abs() + 1e-30).float().mean()) == 1.0

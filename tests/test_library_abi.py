@@ -113,15 +113,20 @@ def test_flags_word_is_validated(lib):
     P = 0x1000
     def fwd(flags):
         return lib.sp_attn_fwd_batched_ex(P, P, P, P, P, 1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, B.SP_SCHED_SHARED,
-                                          flags, None, 0, None)
+                                          flags, None, None, 0, None)
     def bwd(flags):
         return lib.sp_attn_bwd_batched_ex(P, P, P, P, P, P, P, P, P, 1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, 7, flags,
-                                          None, 0, None)
+                                          None, None, 0, None)
     assert fwd(4) == B.SP_ERR_INVALID_ARG and bwd(8) == B.SP_ERR_INVALID_ARG
     assert fwd(B.SP_FLAG_ACCUMULATE_DKDV) == B.SP_ERR_INVALID_ARG
     # valid flags pass the flag check and fail later, at the (missing) workspace
     assert fwd(B.SP_FLAG_RESPONSE_ROWS) == B.SP_ERR_WORKSPACE
     assert bwd(B.SP_FLAG_RESPONSE_ROWS | B.SP_FLAG_ACCUMULATE_DKDV) == B.SP_ERR_WORKSPACE
+    # the optional residual tensor: alignment, and bf16 only
+    assert lib.sp_attn_fwd_batched_ex(P, P, P, P, P, 1, one, g, r, 4, 2, 128, 0.1, B.SP_BF16, B.SP_SCHED_SHARED, 0,
+                                      0x1008, P, 1 << 20, None) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_fwd_batched_ex(P, P, P, P, P, 1, one, g, r, 4, 2, 64, 0.1, B.SP_F32, B.SP_SCHED_SHARED, 0,
+                                      P, P, 1 << 20, None) == B.SP_ERR_UNSUPPORTED
 
 
 def test_loss_calls_reject_bad_arguments(lib):
