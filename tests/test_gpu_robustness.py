@@ -138,3 +138,43 @@ def test_permuting_responses_permutes_outputs():
     gate("dQ rows", to64(dq[idx]), to64(dq2), torch.bfloat16)
     gate("dK prompt", to64(dk[:200]), to64(dk2[:200]), torch.bfloat16)
     gate("dV prompt", to64(dv[:200]), to64(dv2[:200]), torch.bfloat16)
+
+
+def test_forward_and_backward_replay_from_a_captured_graph():
+    """The calls allocate nothing, never synchronise and launch kernels only (the segment table
+    travels as kernel arguments), so a forward+backward can be captured into a graph.  Each replay,
+    with eager work between the replays, must give bit for bit the eager result."""
+    w = W.Workload("graph", [W.Group(333, [1, 63, 65, 0, 127, 129, 200]), W.Group(70, [300, 5])], 6, 2, 128,
+                   torch.bfloat16, 95)
+    t = W.make_tensors(w)
+    q, k, v, d_o = (x.cuda() for x in (t.q, t.k, t.v, t.d_o))
+    pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
+    T, Hq, Hkv, d = w.total_tokens, w.n_q_heads, w.n_kv_heads, w.head_dim
+    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, Hkv, d, B.SP_BF16), dtype=torch.uint8, device="cuda")
+    o, lse = torch.empty_like(q), torch.empty(Hq, T, dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+
+    def run():
+        B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, sc, o=o, lse=lse, workspace=ws)
+        B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc, dq=dq, dk=dk, dv=dv, workspace=ws)
+
+    run()
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (o, lse, dq, dk, dv)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run()
+    for rep in range(3):
+        for x in (o, lse, dq, dk, dv):
+            x.fill_(float(rep))                 # eager work between replays: clobber the outputs
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((o, lse, dq, dk, dv), want):
+            assert torch.equal(got, ref), rep
