@@ -130,6 +130,8 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.o_out = o_out; p.lse_out = lse_out; p.dq = dq; p.dk = dk; p.dv = dv;
     p.tab = (const int*)workspace;
     p.Dbuf = (float*)((char*)workspace + align256(L.words.size() * 4));
+    p.dkdv_partial = (bwd && dtype == SP_BF16 && sp::dkdv_head_split(L.total_tokens, n_groups, Hq, Hkv))
+                         ? (float*)((char*)p.Dbuf + align256((size_t)Hq * (size_t)L.total_tokens * 8)) : nullptr;
     p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
     p.Hq = Hq; p.Hkv = Hkv; p.head_dim = d; p.scale = scale;
     p.naive = schedule == SP_SCHED_NAIVE_CAUSAL;
@@ -155,10 +157,13 @@ extern "C" {
 
 size_t sp_attn_workspace_bytes(int is_bwd, int64_t total_tokens, int32_t n_groups, int64_t total_responses,
                                int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, sp_dtype dtype) {
-    (void)n_kv_heads; (void)head_dim; (void)dtype;
+    (void)head_dim;
     if (total_tokens < 1 || n_groups < 1 || total_responses < 0 || n_q_heads < 1) return 0;
     size_t bytes = align256(table_words(n_groups, total_responses) * 4);
     if (is_bwd) bytes += align256((size_t)n_q_heads * (size_t)total_tokens * 8);   // D and scaled LSE
+    if (is_bwd && dtype == SP_BF16 && n_kv_heads > 0 && n_q_heads % n_kv_heads == 0 &&
+        sp::dkdv_head_split(total_tokens, n_groups, n_q_heads, n_kv_heads))       // per-q-head dK, dV partials
+        bytes += align256((size_t)2 * (n_q_heads / n_kv_heads) * (size_t)total_tokens * n_kv_heads * 128 * 4);
     return bytes;
 }
 

@@ -31,6 +31,10 @@ struct BwdArgs {
     float scale, c;      // c = scale * log2(e)
     int resp_only;       // only response rows are computed (dq) / contribute (dk, dv)
     int accumulate;      // dk, dv are added to what the output buffers hold
+    // dkdv pass on small problems: one workgroup per (key tile, Q head) instead of per (key tile,
+    // kv head); the per-q-head partial sums go to `partial` in fp32 and a second kernel adds them
+    int head_split;
+    float* partial;      // [2 (dK, dV)][rep][T_total][Hkv][128] fp32
 };
 
 // ------------------------------------------------------------------------------------
@@ -319,8 +323,13 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[2][2 * TILE_BYTES];   // [buffer][Q | dO]
     __shared__ __attribute__((aligned(256))) float ldsLD[2][2][BQ];          // [buffer][L2 | D][row]
 
-    int tile, kvh;
-    if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
+    int tile, kvh, hr_only = 0;
+    if (a.head_split) {
+        int head;
+        if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
+        kvh = head / (a.Hq / a.Hkv);
+        hr_only = head % (a.Hq / a.Hkv);
+    } else if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
     // key tiles in ascending order: the first prompt tile is seen by every row (most work)
     int g, s0;
     {
@@ -362,7 +371,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     const int s_lo = max(s, row_lo);                   // first row that contributes to this lane's key
     const int qt0 = max(s0, row_lo) / BQ, qt1 = (row_end + BQ - 1) / BQ;
     const int nqt = max(qt1 - qt0, 0);
-    const int rep = a.Hq / a.Hkv;
+    const int rep_all = a.Hq / a.Hkv;
+    const int rep = a.head_split ? 1 : rep_all;        // q heads this workgroup walks
     const int total = nqt * rep;
     const int64_t q_stride = (int64_t)a.Hq * 128;
     const int64_t kv_stride = (int64_t)a.Hkv * 128;
@@ -406,9 +416,10 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     auto lds_u32 = [](const void* p) -> unsigned {
         return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)p);
     };
-    // q head 0 of this kv head, token 0 of the group
-    const uint64_t qbase_s = sgpr64(a.q + ((int64_t)gd.tok_base * a.Hq + (int64_t)kvh * rep) * 128);
-    const uint64_t gbase_s = sgpr64(a.d_o + ((int64_t)gd.tok_base * a.Hq + (int64_t)kvh * rep) * 128);
+    // first q head of this workgroup, token 0 of the group
+    const int head0 = kvh * rep_all + hr_only;          // first q head this workgroup walks
+    const uint64_t qbase_s = sgpr64(a.q + ((int64_t)gd.tok_base * a.Hq + head0) * 128);
+    const uint64_t gbase_s = sgpr64(a.d_o + ((int64_t)gd.tok_base * a.Hq + head0) * 128);
     const unsigned m0buf[2] = {lds_u32(lds[0]) + 2048u * w, lds_u32(lds[1]) + 2048u * w};
     const unsigned tile_bytes = BQ * qstride_b;
     auto issue_tile = [&](int qt, int hr, int buf) {
@@ -430,7 +441,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
             }
         }
         if (w < 2) {        // wave 0: scaled LSE of the 64 rows, wave 1: D (the first wave of a SIMD has slack)
-            const int head = kvh * rep + hr;
+            const int head = head0 + hr;
             const int t = min(qt * BQ + l, Tg - 1);
             const float* src = (w == 0 ? a.L2 : a.D) + (int64_t)head * T_total + gd.tok_base + t;
             async_copy4(src, reinterpret_cast<char*>(&ldsLD[buf][w][0]));
@@ -631,6 +642,13 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const f32x4 y = *reinterpret_cast<const f32x4*>(xch + (db * 4 + gq) * 256);
+                    if (a.head_split) {      // fp32 partial sum of this q head; scaled and rounded by the reduce kernel
+                        float* part = a.partial + ((int64_t)pass * rep_all + hr_only) * T_total * a.Hkv * 128;
+                        const f32x4 z = {acc[db][4 * gq] + y[0], acc[db][4 * gq + 1] + y[1], acc[db][4 * gq + 2] + y[2],
+                                         acc[db][4 * gq + 3] + y[3]};
+                        *reinterpret_cast<f32x4*>(part + orow + 32 * db + 8 * gq) = z;
+                        continue;
+                    }
                     bf16x4 x;
                     bf16x4 old = {0, 0, 0, 0};
                     if (a.accumulate) old = *reinterpret_cast<const bf16x4*>(out + orow + 32 * db + 8 * gq);
@@ -639,6 +657,34 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
                     *reinterpret_cast<bf16x4*>(out + orow + 32 * db + 8 * gq) = x;
                 }
         }
+    }
+}
+
+// Second stage of the head-split dkdv pass: dk = scale * sum_hr partial[0][hr], dv = sum_hr
+// partial[1][hr], summed in a fixed order (bitwise repeatable), rounded once, optionally added
+// to what the outputs hold.  One thread per 4 consecutive elements.
+__global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restrict__ partial, __bf16* __restrict__ dk,
+                                                          __bf16* __restrict__ dv, int64_t n4, int rep, float scale,
+                                                          int accumulate) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const int64_t plane = n4 * 4;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int hr = 0; hr < rep; ++hr) {
+            const f32x4 x = *reinterpret_cast<const f32x4*>(partial + ((int64_t)pass * rep + hr) * plane + 4 * i);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += x[e];
+        }
+        __bf16* out = (pass == 0 ? dk : dv) + 4 * i;
+        const float mul = pass == 0 ? scale : 1.0f;
+        bf16x4 old = {0, 0, 0, 0};
+        if (accumulate) old = *reinterpret_cast<const bf16x4*>(out);
+        bf16x4 r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = (__bf16)(acc[e] * mul + (float)old[e]);
+        *reinterpret_cast<bf16x4*>(out) = r;
     }
 }
 
@@ -666,8 +712,18 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     }
     if (p.stages & STAGE_DKDV) {
         a.n_tiles = count_tiles(p, 128);
-        const int grid = grid_for_items(a.n_tiles, p.Hkv, p.Hkv);
-        hipLaunchKernelGGL(bwd_dkdv_kernel, dim3(grid), dim3(512), 0, s, a);
+        a.head_split = p.dkdv_partial != nullptr;
+        a.partial = p.dkdv_partial;
+        if (a.head_split) {
+            const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
+            hipLaunchKernelGGL(bwd_dkdv_kernel, dim3(grid), dim3(512), 0, s, a);
+            const int64_t n4 = p.total_tokens * p.Hkv * 32;
+            hipLaunchKernelGGL(dkdv_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, a.partial, a.dk, a.dv,
+                               n4, p.Hq / p.Hkv, p.scale, a.accumulate);
+        } else {
+            const int grid = grid_for_items(a.n_tiles, p.Hkv, p.Hkv);
+            hipLaunchKernelGGL(bwd_dkdv_kernel, dim3(grid), dim3(512), 0, s, a);
+        }
         e = hipGetLastError();
     }
     return e;

@@ -31,6 +31,7 @@ struct Problem {
     void* o_lo_out;                                       // forward (bf16): optional rounding residual of o
     const void* o_lo;                                     // backward (bf16): optional residual for D
     int accumulate;                                       // backward: dk, dv += instead of =
+    float* dkdv_partial;                                  // bf16 backward on small problems: fp32 per-q-head partials
     // host copies of the per-group token counts, for grid sizing
     const int* host_group_tokens;
 };
@@ -55,6 +56,13 @@ inline int count_tiles(const Problem& p, int bm) {
     int n = 0;
     for (int g = 0; g < p.n_groups; ++g) n += (p.host_group_tokens[g] + bm - 1) / bm;
     return n;
+}
+
+// Small problems leave most CUs idle in the dkdv pass (one workgroup per 128 keys and kv head):
+// below this many workgroups the pass is split over the q heads of each kv head, through fp32
+// partial sums in the workspace.  Both the workspace size and the launch use this rule.
+inline bool dkdv_head_split(int64_t total_tokens, int n_groups, int Hq, int Hkv) {
+    return Hq > Hkv && (total_tokens / 128 + n_groups) * Hkv <= 192;
 }
 
 }  // namespace sp
