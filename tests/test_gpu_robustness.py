@@ -178,3 +178,38 @@ def test_forward_and_backward_replay_from_a_captured_graph():
         torch.cuda.synchronize()
         for got, ref in zip((o, lse, dq, dk, dv), want):
             assert torch.equal(got, ref), rep
+
+
+@pytest.mark.parametrize("gain", [6.0, 20.0])
+def test_large_logits_keep_the_softmax_in_range(gain):
+    """Scores with a standard deviation of tens to hundreds: rows are near one-hot, the row maximum
+    jumps by hundreds of units between tiles (every jump takes the forward's re-reference path) and
+    exp underflows everywhere else.  Outputs must stay finite and at the usual tolerances.  dQ is
+    the exception on the plain entry points: in a one-hot row dS = P (dP - D) cancels to almost
+    nothing and D = rowsum(dO * o) carries the bf16 rounding of o, so dQ is held to the gates only
+    when the forward hands the rounding residual of o to the backward (o_lo), and to twice the
+    relative-RMS gate otherwise."""
+    w = W.Workload("hot", [W.Group(300, [130, 0, 64, 77])], 4, 2, 128, torch.bfloat16, 99)
+    t = W.make_tensors(w)
+    t.q.mul_(gain)
+    t.k.mul_(gain)
+    pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
+    q, k, v, d_o = (x.cuda() for x in (t.q, t.k, t.v, t.d_o))
+    o_lo = torch.empty_like(q)
+    o, lse = B.sp_attn_fwd_batched_ex(q, k, v, pl, Gs, rl, sc, 0, o_lo=o_lo)
+    dq0, dk0, dv0 = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc)
+    dq, dk, dv = B.sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, pl, Gs, rl, sc, 0, o_lo=o_lo)
+    torch.cuda.synchronize()
+    rdq, rdk, rdv, ro, rlse = oracle_bwd(w, t)
+    assert float(np.abs(rlse).max()) > 4.0 * gain * gain    # the scores really are that large
+    gate("O", to64(o), ro, w.dtype)
+    err = np.abs(to64(lse) - rlse)
+    assert float((err - (1e-4 + 3e-7 * np.abs(rlse))).max()) <= 0.0      # fp32 LSE of magnitude 1e2..1e4
+    gate("dQ[o_lo]", to64(dq), rdq, w.dtype)
+    gate("dK[o_lo]", to64(dk), rdk, w.dtype)
+    gate("dV[o_lo]", to64(dv), rdv, w.dtype)
+    gate("dK", to64(dk0), rdk, w.dtype)
+    gate("dV", to64(dv0), rdv, w.dtype)
+    e0 = to64(dq0) - rdq
+    assert np.all(np.isfinite(e0))
+    assert float(np.sqrt(np.mean(e0 ** 2)) / np.sqrt(np.mean(rdq ** 2))) <= 1e-2
