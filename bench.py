@@ -92,6 +92,9 @@ def main():
                          "over logits [T, 151936] generated on the device")
     ap.add_argument("--rope", action="store_true",
                     help="also time the rotary-embedding pass (restarted positions) over q and k")
+    ap.add_argument("--cold", action="store_true",
+                    help="overwrite a 1 GiB buffer before every step so that L2 and the Infinity Cache hold none of "
+                         "the inputs; throughput is then taken from the summed stage times, not the wall clock")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -144,6 +147,7 @@ def main():
                                          dk=dk, dv=dv)
             mark(4)
 
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev) if args.cold else None
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -152,6 +156,8 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
+        if flush is not None:
+            flush.fill_(i & 0xFF)
         step(evs[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -159,6 +165,8 @@ def main():
     stage_ms = {}
     for si, name in enumerate(stage_names):
         stage_ms[name] = sum(evs[i][si].elapsed_time(evs[i][si + 1]) for i in range(args.steps)) / args.steps
+    if flush is not None:
+        ms_per_step = sum(stage_ms.values())
 
     fwd_flops = W.useful_flops(w, False) / w.n_sets
     bwd_flops = W.useful_flops(w, True) / w.n_sets if do_bwd else 0.0
@@ -180,6 +188,8 @@ def main():
                 "pct_peak": round(100.0 * fwd_tf / PEAK_BF16_TFLOPS, 2)},
         "stage_ms": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
     }
+    if flush is not None:
+        out["cold_cache"] = True
     if do_bwd:
         bwd_ms = stage_ms["bwd_rowsum"] + stage_ms["bwd_dkdv"] + stage_ms["bwd_dq"]
         bwd_tf = bwd_flops / (bwd_ms * 1e-3) / 1e12
