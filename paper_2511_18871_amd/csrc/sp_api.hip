@@ -65,13 +65,14 @@ sp_status build_table(int32_t n_groups, const int32_t* prompt_lens, const int32_
     L.total_responses = nresp;
     L.words.assign(table_words(n_groups, nresp), 0);
     L.group_tokens.resize(n_groups);
-    int64_t tok = 0, r = 0;
+    int64_t tok = 0, r = 0, tiles256 = 0, tiles128 = 0;
     size_t roff = (size_t)sp::TAB_HEADER + (size_t)sp::TAB_GROUP_WORDS * n_groups;
     for (int g = 0; g < n_groups; ++g) {
         if (prompt_lens[g] < 0) return fail(SP_ERR_INVALID_ARG, "group %d: prompt_len is negative", g);
         int64_t tg = prompt_lens[g];
         int32_t* e = &L.words[sp::TAB_HEADER + sp::TAB_GROUP_WORDS * g];
         e[0] = (int32_t)tok; e[1] = prompt_lens[g]; e[3] = (int32_t)roff; e[4] = Gs[g];
+        e[sp::TAB_TILES256] = (int32_t)tiles256; e[sp::TAB_TILES128] = (int32_t)tiles128;
         L.words[roff++] = prompt_lens[g];
         for (int i = 0; i < Gs[g]; ++i, ++r) {
             if (resp_lens_flat[r] < 0) return fail(SP_ERR_INVALID_ARG, "group %d: response %d has negative length", g, i);
@@ -84,6 +85,7 @@ sp_status build_table(int32_t n_groups, const int32_t* prompt_lens, const int32_
         L.group_tokens[g] = (int)tg;
         if (tg > L.max_group_tokens) L.max_group_tokens = (int)tg;
         tok += tg;
+        tiles256 += (tg + 255) / 256; tiles128 += (tg + 127) / 128;
         if (tok > 0x7fff0000LL) return fail(SP_ERR_INVALID_ARG, "total token count exceeds the int32 range");
     }
     L.total_tokens = tok;

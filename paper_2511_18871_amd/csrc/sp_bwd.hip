@@ -50,11 +50,12 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
 
     int tile, head;
     if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
-    int g, t0;
-    find_tile(a.tab, tile, BM, g, t0);
+    int g, ti;
+    find_tile<BM>(a.tab, tile, g, ti);
     if (g < 0) return;
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;
+    const int t0 = ((Tg + BM - 1) / BM - 1 - ti) * BM;   // a group's last tile first: it carries the most work
     const int64_t T_total = a.tab[1];
     if (a.resp_only && t0 + BM <= Lp) return;      // a tile of prompt rows only
 
@@ -331,17 +332,9 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         hr_only = head % (a.Hq / a.Hkv);
     } else if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
     // key tiles in ascending order: the first prompt tile is seen by every row (most work)
-    int g, s0;
-    {
-        const int ng = a.tab[0];
-        int base = 0;
-        g = -1; s0 = 0;
-        for (int gi = 0; gi < ng; ++gi) {
-            const int nt = (a.tab[TAB_HEADER + TAB_GROUP_WORDS * gi + 2] + BNK - 1) / BNK;
-            if (tile < base + nt) { g = gi; s0 = (tile - base) * BNK; break; }
-            base += nt;
-        }
-    }
+    int g, ti;
+    find_tile<BNK>(a.tab, tile, g, ti);
+    const int s0 = ti * BNK;
     if (g < 0) return;
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;

@@ -21,12 +21,16 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 // ---------------------------------------------------------------------------
 // Segment table (int32 words, device memory, written by sp_upload_table):
 //   [0] n_groups   [1] total_tokens   [2] table_words   [3] reserved
-//   group g at 4 + 6*g : { tok_base, prompt_len, T_g, roff_idx, G, reserved }
+//   group g at 4 + 8*g : { tok_base, prompt_len, T_g, roff_idx, G, tiles256_before, tiles128_before, reserved }
 //   roff_idx points at G+1 group-local offsets: roff[0] = prompt_len,
 //   roff[i+1] = roff[i] + len(resp_i), roff[G] = T_g.
+//   tilesB_before = sum over earlier groups of ceil(T_g / B): the kernels number their work
+//   tiles (B rows or keys) group by group and find a tile's group by bisection on this word.
 // ---------------------------------------------------------------------------
 constexpr int TAB_HEADER = 4;
-constexpr int TAB_GROUP_WORDS = 6;
+constexpr int TAB_GROUP_WORDS = 8;
+constexpr int TAB_TILES256 = 5;        // word of the group entry: 256-row tiles before this group
+constexpr int TAB_TILES128 = 6;        // 128-key tiles before this group
 constexpr int TAB_CHUNK_WORDS = 960;   // words carried by one upload launch (kernarg limit 4 KB)
 
 struct TabChunk { int32_t w[TAB_CHUNK_WORDS]; };
@@ -70,24 +74,34 @@ __device__ __forceinline__ int seg_end(const GroupDesc& d, int t) {
     return d.roff[lo + 1];
 }
 
-// Work-tile lookup: tiles of `bm` rows are numbered group by group; inside a group the
-// LAST tile comes first (response tiles and late prompt tiles carry the most work, so
-// launch order is roughly longest-first).  Returns the group and the tile's first row.
-__device__ __forceinline__ void find_tile(const int* __restrict__ tab, int tile, int bm,
-                                          int& g_out, int& t0_out) {
-    const int ng = tab[0];
-    int g = 0, base = 0;
-    for (; g < ng; ++g) {
-        const int Tg = tab[TAB_HEADER + TAB_GROUP_WORDS * g + 2];
-        const int nt = (Tg + bm - 1) / bm;
-        if (tile < base + nt) {
-            g_out = g;
-            t0_out = (nt - 1 - (tile - base)) * bm;
-            return;
-        }
-        base += nt;
+// Group that owns packed token tok (0 <= tok < total_tokens): bisection on tok_base.
+__device__ __forceinline__ int find_group_of_token(const int* __restrict__ tab, int64_t tok) {
+    int lo = 0, hi = tab[0];           // invariant: tok_base[lo] <= tok, (hi == n_groups or tok_base[hi] > tok)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tab[TAB_HEADER + TAB_GROUP_WORDS * mid] <= tok) lo = mid; else hi = mid;
     }
-    g_out = -1; t0_out = 0;
+    return lo;
+}
+
+// Work-tile lookup: tiles of BT rows (256) or keys (128) are numbered group by group.  Returns
+// the group and the tile's index inside it (0 .. ceil(T_g / BT) - 1), or g_out = -1 when the
+// tile number lies past the last group.  Bisection on the group entries' running tile counts,
+// so a batch of many small groups costs log2(n_groups) dependent scalar loads per workgroup.
+template <int BT>
+__device__ __forceinline__ void find_tile(const int* __restrict__ tab, int tile, int& g_out, int& idx_out) {
+    static_assert(BT == 256 || BT == 128, "the table carries running tile counts for 256 and 128 only");
+    constexpr int W = BT == 256 ? TAB_TILES256 : TAB_TILES128;
+    int lo = 0, hi = tab[0];
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tab[TAB_HEADER + TAB_GROUP_WORDS * mid + W] <= tile) lo = mid; else hi = mid;
+    }
+    const int* e = tab + TAB_HEADER + TAB_GROUP_WORDS * lo;
+    const int idx = tile - e[W];
+    const int nt = (e[2] + BT - 1) / BT;
+    g_out = idx < nt ? lo : -1;
+    idx_out = idx;
 }
 
 // Map a flat block index to (tile, q head) so that the blocks an XCD receives

@@ -21,14 +21,6 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-// group that owns packed token tok
-__device__ __forceinline__ int find_group(const int* __restrict__ tab, int tok) {
-    const int ng = tab[0];
-    int g = 0;
-    while (g + 1 < ng && tab[TAB_HEADER + TAB_GROUP_WORDS * (g + 1)] <= tok) ++g;
-    return g;
-}
-
 __global__ void upload_table_kernel(TabChunk chunk, int* __restrict__ dst, int offset, int count) {
     for (int i = threadIdx.x; i < count; i += blockDim.x) dst[offset + i] = chunk.w[i];
 }
@@ -47,7 +39,7 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, 
     if (resp_only) {
         // prompt rows take no part: their o / lse may hold anything, so they are not read, and the
         // planes get finite placeholders (rows of a partly used tile are masked, not skipped)
-        const GroupDesc gd = load_group(tab, find_group(tab, (int)tok));
+        const GroupDesc gd = load_group(tab, find_group_of_token(tab, (int)tok));
         if ((int)tok - gd.tok_base < gd.Lp) {
             if (l == 0) {
                 D[(int64_t)h * T_total + tok] = 0.f;
@@ -92,7 +84,7 @@ __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ 
     const int l = threadIdx.x & 63;
     if (gw >= T_total * Hq) return;
     const int tok = (int)(gw / Hq), h = (int)(gw % Hq);
-    const GroupDesc gd = load_group(tab, find_group(tab, tok));
+    const GroupDesc gd = load_group(tab, find_group_of_token(tab, tok));
     const int t = tok - gd.tok_base;
     if (resp_only && t < gd.Lp) return;
     const int st = seg_start(gd, t);
@@ -145,7 +137,7 @@ __global__ __launch_bounds__(256) void bwd_dq_f32_kernel(const float* __restrict
     const int l = threadIdx.x & 63;
     if (gw >= T_total * Hq) return;
     const int tok = (int)(gw / Hq), h = (int)(gw % Hq);
-    const GroupDesc gd = load_group(tab, find_group(tab, tok));
+    const GroupDesc gd = load_group(tab, find_group_of_token(tab, tok));
     const int t = tok - gd.tok_base;
     if (resp_only && t < gd.Lp) return;
     const int st = seg_start(gd, t);
@@ -199,7 +191,7 @@ __global__ __launch_bounds__(256) void bwd_dkdv_f32_kernel(const float* __restri
     const int l = threadIdx.x & 63;
     if (gw >= T_total * Hkv) return;
     const int tok = (int)(gw / Hkv), kvh = (int)(gw % Hkv);
-    const GroupDesc gd = load_group(tab, find_group(tab, tok));
+    const GroupDesc gd = load_group(tab, find_group_of_token(tab, tok));
     const int s = tok - gd.tok_base;
     const int row_end = s < gd.Lp ? gd.Tg : seg_end(gd, s);
     const int rep = Hq / Hkv;

@@ -62,11 +62,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     __bf16* const ao = a.o[set]; float* const alse = a.lse[set];
     int tile, head;
     if (!decode_item(blockIdx.x - set * a.blocks_per_set, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
-    int g, t0;
-    find_tile(a.tab, tile, BM, g, t0);
+    int g, ti;
+    find_tile<BM>(a.tab, tile, g, ti);
     if (g < 0) return;
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;
+    const int t0 = ((Tg + BM - 1) / BM - 1 - ti) * BM;   // a group's last tile first: it carries the most work
     const int T_total = a.tab[1];
     if (a.resp_only && t0 + BM <= Lp) return;      // a tile of prompt rows only
 

@@ -20,15 +20,6 @@ template <typename T> struct Ld;
 template <> struct Ld<__bf16> { typedef bf16x8 vec; static constexpr int N = 8; };
 template <> struct Ld<float> { typedef f32x4 vec; static constexpr int N = 4; };
 
-__device__ __forceinline__ int find_group_of(const int* __restrict__ tab, int64_t tok) {
-    int lo = 0;
-    for (int hi = tab[0]; hi - lo > 1;) {
-        const int mid = (lo + hi) >> 1;
-        if (tab[TAB_HEADER + TAB_GROUP_WORDS * mid] <= tok) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 // (max, sum of exp(x - max)) merge
 __device__ __forceinline__ void ms_merge(float& m, float& s, float m2, float s2) {
     const float mn = fmaxf(m, m2);
@@ -55,7 +46,7 @@ __global__ __launch_bounds__(256) void logprob_fwd_kernel(const T* __restrict__ 
                                                           const int* __restrict__ tab, int64_t V) {
     __shared__ float sh[8];
     const int64_t tok = blockIdx.x;
-    const GroupDesc gd = load_group(tab, find_group_of(tab, tok));
+    const GroupDesc gd = load_group(tab, find_group_of_token(tab, tok));
     if (tok - gd.tok_base < gd.Lp) return;              // prompt row: discarded
     const T* row = z + tok * V;
     float m = -INFINITY, s = 0.f;
@@ -97,7 +88,7 @@ __global__ __launch_bounds__(256) void logprob_bwd_kernel(const T* __restrict__ 
                                                           const float* __restrict__ lse, const float* __restrict__ g,
                                                           T* __restrict__ dz, const int* __restrict__ tab, int64_t V) {
     const int64_t tok = blockIdx.x;
-    const GroupDesc gd = load_group(tab, find_group_of(tab, tok));
+    const GroupDesc gd = load_group(tab, find_group_of_token(tab, tok));
     if (tok - gd.tok_base < gd.Lp) return;
     const T* row = z + tok * V;
     T* out = dz + tok * V;

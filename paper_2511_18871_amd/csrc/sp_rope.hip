@@ -31,13 +31,7 @@ __global__ __launch_bounds__(256) void rope_kernel(const T* __restrict__ x, T* _
     const int i0 = 8 * (int)(((int64_t)blockIdx.x * 256 + threadIdx.x) % tpt);
     if (tok >= T_total) return;
     // group of the token, then its position index
-    const int ng = tab[0];
-    int g = 0;
-    for (int lo = 0, hi = ng; hi - lo > 1;) {          // groups are sorted by tok_base
-        const int mid = (lo + hi) >> 1;
-        if (tab[TAB_HEADER + TAB_GROUP_WORDS * mid] <= tok) lo = mid; else hi = mid;
-        g = lo;
-    }
+    const int g = find_group_of_token(tab, tok);
     const GroupDesc gd = load_group(tab, g);
     const int t = (int)(tok - gd.tok_base);
     const int pos = t < gd.Lp ? t : gd.Lp + (t - seg_start(gd, t));

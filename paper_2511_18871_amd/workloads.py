@@ -164,3 +164,19 @@ def make_tensors(w: Workload, set_index: int = 0) -> Tensors:
         stressed = torch.nonzero(pick).flatten().tolist()
     cast = lambda x: None if x is None else x.to(w.dtype).contiguous()
     return Tensors(cast(q), cast(k), cast(v), cast(d_o), stressed)
+
+
+def make_tensors_on_device(w: Workload, device) -> Tensors:
+    """The same recipe drawn by the device's generator (seed ``w.seed``; q, k, v, dO in that
+    order, N(0,1) rounded to ``w.dtype``), for packings whose tensors are several GiB each and
+    would take minutes to draw on the host.  A consumer that needs host values copies the
+    slices it wants from these tensors."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w.seed)
+    T, Hq, Hkv, d = w.total_tokens, w.n_q_heads, w.n_kv_heads, w.head_dim
+
+    def draw(heads):
+        return torch.empty(T, heads, d, dtype=w.dtype, device=device).normal_(generator=gen)
+
+    q, k, v = draw(Hq), draw(Hkv), draw(Hkv)
+    return Tensors(q, k, v, draw(Hq) if w.backward else None)
