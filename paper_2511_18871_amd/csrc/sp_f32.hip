@@ -65,6 +65,74 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, 
     }
 }
 
+// The same rowsum for bf16 rows of 128 elements, laid out for bandwidth.  A block owns RS_TOK
+// consecutive tokens x all q heads, which is one contiguous stretch of d_o and of o; 16 lanes read
+// a (token, head) row as 16-byte pieces and add up over the lanes.  The sums pass through LDS so
+// that each head's RS_TOK tokens leave as one contiguous store into the [Hq, T] planes.  In
+// response-rows mode the prompt rows are still read (the buffers are whole) but their values are
+// discarded by a select, never used in arithmetic that reaches the output.
+constexpr int RS_TOK = 16;
+template <bool HAS_LO>
+__global__ __launch_bounds__(256) void rowsum_bf16_kernel(const __bf16* __restrict__ d_o, const __bf16* __restrict__ o,
+                                                          const float* __restrict__ lse, float* __restrict__ D,
+                                                          int64_t T_total, int Hq, const int* __restrict__ tab,
+                                                          int resp_only, const __bf16* __restrict__ o_lo) {
+    extern __shared__ float rs_sum[];                  // [Hq][RS_TOK]
+    __shared__ int rs_skip[RS_TOK];
+    const int64_t tok0 = (int64_t)blockIdx.x * RS_TOK;
+    const int ntok = (int)(T_total - tok0 < RS_TOK ? T_total - tok0 : RS_TOK);
+    const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4;
+    if (tid < RS_TOK) {
+        int sk = 0;
+        if (resp_only && tid < ntok) {
+            const GroupDesc gd = load_group(tab, find_group_of_token(tab, tok0 + tid));
+            sk = (int)(tok0 + tid - gd.tok_base) < gd.Lp;
+        }
+        rs_skip[tid] = sk;
+    }
+    __syncthreads();
+    const int nrows = ntok * Hq;
+    const int64_t base = tok0 * Hq * 128 + 8 * sub;
+    auto row_dot = [&](int r) -> float {
+        const int64_t off = base + (int64_t)r * 128;
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(d_o + off);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(o + off);
+        float acc = 0.f;
+        if (HAS_LO) {        // o was stored with its rounding residual: D from the unrounded value
+            const bf16x8 c = *reinterpret_cast<const bf16x8*>(o_lo + off);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)a[e], (float)b[e] + (float)c[e], acc);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)a[e], (float)b[e], acc);
+        }
+        return acc;
+    };
+    auto put = [&](int r, float acc) {
+#pragma unroll
+        for (int sh = 8; sh >= 1; sh >>= 1) acc += __shfl_xor(acc, sh, 16);
+        const int tl = r / Hq, h = r - tl * Hq;
+        if (sub == 0) rs_sum[h * RS_TOK + tl] = rs_skip[tl] ? 0.f : acc;
+    };
+    for (int r = grp; r < nrows; r += 32) {            // two rows per trip: four to six loads in flight per lane
+        const bool two = r + 16 < nrows;
+        const float x0 = row_dot(r), x1 = row_dot(two ? r + 16 : r);
+        put(r, x0);
+        if (two) put(r + 16, x1);
+    }
+    __syncthreads();
+    for (int i = tid; i < Hq * RS_TOK; i += 256) {
+        const int h = i / RS_TOK, tl = i % RS_TOK;
+        if (tl < ntok) {
+            const int64_t idx = (int64_t)h * T_total + tok0 + tl;
+            D[idx] = rs_sum[i];
+            // second plane: the row's logsumexp in base-2 units, as the MFMA backward consumes it
+            const float l2 = lse[idx] * LOG2E;
+            D[(int64_t)Hq * T_total + idx] = rs_skip[tl] ? 0.f : l2;
+        }
+    }
+}
+
 template <int DH>
 __device__ __forceinline__ float dot_row(const float* __restrict__ x, const float* __restrict__ y) {
     float acc = 0.f;
@@ -255,6 +323,16 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
     if (f32)
         hipLaunchKernelGGL(rowsum_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)p.d_o,
                            (const float*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only, (const float*)nullptr);
+    else if (p.head_dim == 128 && (size_t)p.Hq * RS_TOK * sizeof(float) <= 32768) {
+        const dim3 g((unsigned)((p.total_tokens + RS_TOK - 1) / RS_TOK));
+        const size_t lds = (size_t)p.Hq * RS_TOK * sizeof(float);
+        if (p.o_lo)
+            hipLaunchKernelGGL(rowsum_bf16_kernel<true>, g, dim3(256), lds, s, (const __bf16*)p.d_o, (const __bf16*)p.o,
+                               p.lse, p.Dbuf, p.total_tokens, p.Hq, p.tab, p.resp_only, (const __bf16*)p.o_lo);
+        else
+            hipLaunchKernelGGL(rowsum_bf16_kernel<false>, g, dim3(256), lds, s, (const __bf16*)p.d_o, (const __bf16*)p.o,
+                               p.lse, p.Dbuf, p.total_tokens, p.Hq, p.tab, p.resp_only, (const __bf16*)nullptr);
+    }
     else
         hipLaunchKernelGGL(rowsum_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)p.d_o,
                            (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only, (const __bf16*)p.o_lo);
