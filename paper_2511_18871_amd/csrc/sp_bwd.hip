@@ -65,22 +65,33 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     const int t = t0 + 32 * w + c;
     const bool valid = t < Tg;
     const int tm = valid ? t : -1;
-    const int st = valid ? seg_start(gd, t) : 0;
     const int tw0 = t0 + 32 * w;
     const bool wave_valid = tw0 < Tg;
     const int tw1 = min(tw0 + 31, Tg - 1);
-    const int st_last = wave_valid ? __builtin_amdgcn_readfirstlane(seg_start(gd, tw1)) : 0;
+    // segment starts of this lane's row and of the workgroup's first response row, one search
+    int st, b2;
+    {
+        const int first_resp = min(max(t0, Lp), Tg - 1);
+        const int tq[2] = {max(min(t, Tg - 1), Lp), max(first_resp, Lp)};
+        int sq[2], eq[2];
+        seg_bounds<2>(gd, tq, sq, eq);
+        st = (valid && t >= Lp) ? sq[0] : 0;
+        b2 = __builtin_amdgcn_readfirstlane(first_resp < Lp ? 0 : sq[1]);
+    }
+    // lanes 0..31 hold the wave's rows in order: the last valid row's start comes from its lane
+    const int st_last = wave_valid ? __builtin_amdgcn_readlane(st, tw1 - tw0) : 0;
 
     bf16x8 qreg[8], goreg[8];
     float Lq = 0.f, Dq = 0.f;
     {
-        const int64_t row = ((int64_t)(gd.tok_base + (valid ? t : 0)) * a.Hq + head) * 128 + 8 * hh;
+        // rows past the end of the group read the group's last row: their scores are all masked
+        // (P = dS = 0 whatever q and dO hold, and a non-finite dO there only reaches dq rows that are
+        // not stored); no select on the loaded values, so the loads are not waited for here
+        const int64_t row = ((int64_t)(gd.tok_base + min(t, Tg - 1)) * a.Hq + head) * 128 + 8 * hh;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            bf16x8 x = *reinterpret_cast<const bf16x8*>(a.q + row + 16 * ks);
-            bf16x8 y = *reinterpret_cast<const bf16x8*>(a.d_o + row + 16 * ks);
-            if (!valid) { x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0}; y = x; }
-            qreg[ks] = x; goreg[ks] = y;
+            qreg[ks] = *reinterpret_cast<const bf16x8*>(a.q + row + 16 * ks);
+            goreg[ks] = *reinterpret_cast<const bf16x8*>(a.d_o + row + 16 * ks);
         }
         if (valid) {
             Lq = a.L2[(int64_t)head * T_total + gd.tok_base + t];
@@ -91,7 +102,6 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     const int t1 = min(t0 + BM, Tg);
     int n1 = (min(Lp, t1) + BN - 1) / BN, k2b = n1, k2e = n1;
     if (t1 > Lp) {
-        const int b2 = seg_start(gd, max(t0, Lp));
         k2b = max(n1, b2 / BN);
         k2e = (t1 + BN - 1) / BN;
     }
@@ -347,18 +357,24 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     // this lane's key (a column of S) and the rows [s, e_s) that may see it
     const int s = s0 + 32 * kb + c;
     const bool valid = s < Tg;
-    const int e_s = !valid ? 0 : (s < Lp ? Tg : seg_end(gd, s));
     const int ws0 = s0 + 32 * kb;                      // wave's first key
     const bool wave_valid = ws0 < Tg;
     const int ws1 = min(ws0 + 31, Tg - 1);             // wave's last valid key
-    // smallest / largest row bound e_s over the wave's keys (prompt keys: Tg; response
-    // keys: the end of their response, non-decreasing in s)
-    const int e_min = !wave_valid ? 0 : (ws1 < Lp ? Tg : seg_end(gd, max(ws0, Lp)));
-    const int e_max = !wave_valid ? 0 : (ws0 < Lp ? Tg : seg_end(gd, ws1));
-
-    // rows that see any key of the workgroup's tile
     const int s1 = min(s0 + BNK, Tg);
-    const int row_end = s0 < Lp ? Tg : seg_end(gd, s1 - 1);
+    // segment ends of this lane's key and of the workgroup's last key, found in one search
+    int e_s, row_end;                                  // row_end: rows that see any key of the tile end here
+    {
+        const int tq[2] = {max(min(s, Tg - 1), Lp), max(s1 - 1, Lp)};
+        int sq[2], eq[2];
+        seg_bounds<2>(gd, tq, sq, eq);
+        e_s = !valid ? 0 : (s < Lp ? Tg : eq[0]);
+        row_end = __builtin_amdgcn_readfirstlane(s0 < Lp ? Tg : eq[1]);
+    }
+    // smallest / largest row bound e_s over the wave's keys (prompt keys: Tg; response keys: the
+    // end of their response, non-decreasing in s); lanes 0..31 hold the wave's keys in order
+    const int e_min = !wave_valid ? 0 : (ws1 < Lp ? Tg : __builtin_amdgcn_readlane(e_s, max(ws0, Lp) - ws0));
+    const int e_max = !wave_valid ? 0 : (ws0 < Lp ? Tg : __builtin_amdgcn_readlane(e_s, ws1 - ws0));
+
     // with only response rows contributing, the rows start at the end of the prompt
     const int row_lo = a.resp_only ? Lp : 0;
     const int s_lo = max(s, row_lo);                   // first row that contributes to this lane's key

@@ -74,6 +74,30 @@ __device__ __forceinline__ int seg_end(const GroupDesc& d, int t) {
     return d.roff[lo + 1];
 }
 
+// Segment bounds [st, en) of N group-local response tokens at once (every t[n] must satisfy
+// Lp <= t[n] < Tg; for a prompt token the caller substitutes its own bounds).  One descending-step
+// search over the response offsets per token, all N advanced in lock-step with unconditional
+// loads, so the N dependent load chains overlap instead of following one another.  st is the last
+// accepted offset; en is the last rejected one (the probes that fail come at ever smaller indices,
+// the last of them is the accepted index + 1), so neither needs a load after the search.
+template <int N>
+__device__ __forceinline__ void seg_bounds(const GroupDesc& d, const int (&t)[N], int (&st)[N], int (&en)[N]) {
+    int pos[N];
+#pragma unroll
+    for (int n = 0; n < N; ++n) { pos[n] = 0; st[n] = d.Lp; en[n] = d.Tg; }
+    for (int step = d.G > 0 ? 1 << (31 - __clz(d.G)) : 0; step >= 1; step >>= 1) {
+        int val[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) val[n] = d.roff[pos[n] + step < d.G ? pos[n] + step : 0];
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            const bool in = pos[n] + step < d.G;
+            if (in && val[n] <= t[n]) { pos[n] += step; st[n] = val[n]; }
+            else if (in) en[n] = val[n];
+        }
+    }
+}
+
 // Group that owns packed token tok (0 <= tok < total_tokens): bisection on tok_base.
 __device__ __forceinline__ int find_group_of_token(const int* __restrict__ tab, int64_t tok) {
     int lo = 0, hi = tab[0];           // invariant: tok_base[lo] <= tok, (hi == n_groups or tok_base[hi] > tok)

@@ -77,21 +77,30 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     const int t = t0 + 32 * w + c;
     const bool valid = t < Tg;
     const int tm = valid ? t : -1;
-    const int st = valid ? seg_start(gd, t) : 0;
     const int tw0 = t0 + 32 * w;
     const bool wave_valid = tw0 < Tg;
     const int tw1 = min(tw0 + 31, Tg - 1);
-    const int st_last = wave_valid ? __builtin_amdgcn_readfirstlane(seg_start(gd, tw1)) : 0;
+    // segment starts of this lane's row and of the workgroup's first response row, one search
+    int st, b2;
+    {
+        const int first_resp = min(max(t0, Lp), Tg - 1);
+        const int tq[2] = {max(min(t, Tg - 1), Lp), max(first_resp, Lp)};
+        int sq[2], eq[2];
+        seg_bounds<2>(gd, tq, sq, eq);
+        st = (valid && t >= Lp) ? sq[0] : 0;
+        b2 = __builtin_amdgcn_readfirstlane(first_resp < Lp ? 0 : sq[1]);
+    }
+    // lanes 0..31 hold the wave's rows in order: the last valid row's start comes from its lane
+    const int st_last = wave_valid ? __builtin_amdgcn_readlane(st, tw1 - tw0) : 0;
 
     bf16x8 qreg[8];
     {
-        const __bf16* qp = aq + ((int64_t)(gd.tok_base + (valid ? t : 0)) * a.Hq + head) * 128 + 8 * hh;
+        // rows past the end of the group read the group's last row instead: every score of such a
+        // row is masked and nothing of it is stored, and without a select on the loaded value the
+        // wait for these loads moves down to the first MFMA, behind the issue of the tile copies
+        const __bf16* qp = aq + ((int64_t)(gd.tok_base + min(t, Tg - 1)) * a.Hq + head) * 128 + 8 * hh;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            bf16x8 x = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-            if (!valid) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            qreg[ks] = x;
-        }
+        for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     }
 
     const int t1 = min(t0 + BM, Tg);
@@ -102,7 +111,6 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         n1 = (min(Lp, t1) + BN - 1) / BN;
         k2b = k2e = n1;
         if (t1 > Lp) {
-            const int b2 = seg_start(gd, max(t0, Lp));
             k2b = max(n1, b2 / BN);
             k2e = (t1 + BN - 1) / BN;
         }
@@ -372,27 +380,45 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // LSE uses the unrounded sum.
     const float ltot = pair_sum(lsum);
     const float lrt = pair_sum(lsr);
-    if (valid && !(a.resp_only && t < Lp)) {
-        const float inv = 1.0f / lrt;
-        __bf16* op = ao + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
+    // The K buffers are free from here on (every wave has passed the last barrier and only ldsVb[3]
+    // is still read).  A lane holds 16 pieces of 8 bytes of its row; written to memory directly, one
+    // store instruction would touch 32 rows.  Each wave therefore stages its own 32 rows x 256 B in
+    // its own 8 KB of LDS (swizzled like the operand tiles: two-way conflicts on the 8-byte writes,
+    // which is their minimum, none on the 16-byte reads) and stores whole rows: 16 lanes per row,
+    // four rows per instruction.  No workgroup barrier: a wave reads back only what it wrote.
+    char* const stage = ldsKb[0] + 8192 * w;
+    const float inv = 1.0f / lrt;
+    // lane indices re-derived behind an opaque barrier: the addresses below are loop-invariant, and
+    // hoisted above the main loop they would cost it registers
+    int lz = l;
+    asm volatile("" : "+v"(lz));
+    auto store_rows = [&, c = lz & 31, hh = lz >> 5, l = lz](__bf16* dst, auto value) {
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
                 bf16x4 x;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) x[e] = (__bf16)(oacc[db][4 * gq + e] * inv);
-                *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * gq) = x;
-                if (a.o_lo) {        // what the rounding of o dropped: lets the backward form D from an unrounded o
-                    bf16x4 r;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) r[e] = (__bf16)(oacc[db][4 * gq + e] * inv - (float)x[e]);
-                    *reinterpret_cast<bf16x4*>(a.o_lo + (op - ao) + 32 * db + 8 * gq) = r;
-                }
+                for (int e = 0; e < 4; ++e) x[e] = value(db, 4 * gq + e);
+                *reinterpret_cast<bf16x4*>(stage + tile_off(c, 4 * db + gq) + 8 * hh) = x;
             }
-        if (hh == 0)
-            alse[(int64_t)head * T_total + gd.tok_base + t] = (m * cs + __log2f(ltot)) * LN2;
-    }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + (l >> 4);
+            const bf16x8 x = lds_read_row8(stage, r, l & 15);
+            const int tr = tw0 + r;
+            if (tr < Tg && !(a.resp_only && tr < Lp))
+                *reinterpret_cast<bf16x8*>(dst + ((int64_t)(gd.tok_base + tr) * a.Hq + head) * 128 + 8 * (l & 15)) = x;
+        }
+    };
+    store_rows(ao, [&](int db, int r) { return (__bf16)(oacc[db][r] * inv); });
+    if (a.o_lo)              // what the rounding of o dropped: lets the backward form D from an unrounded o
+        store_rows(a.o_lo, [&](int db, int r) {
+            const float x = oacc[db][r] * inv;
+            return (__bf16)(x - (float)(__bf16)x);
+        });
+    if (valid && !(a.resp_only && t < Lp) && hh == 0)
+        alse[(int64_t)head * T_total + gd.tok_base + t] = (m * cs + __log2f(ltot)) * LN2;
 }
 
 }  // namespace
