@@ -27,7 +27,7 @@ struct BwdArgs {
     const float* lse; float* D; const float* L2;   // L2 = lse * log2(e), written by the rowsum stage
     __bf16* dq; __bf16* dk; __bf16* dv;
     const int* tab;
-    int n_tiles, Hq, Hkv;
+    int n_tiles, n_groups, Hq, Hkv;
     float scale, c;      // c = scale * log2(e)
     int resp_only;       // only response rows are computed (dq) / contribute (dk, dv)
     int accumulate;      // dk, dv are added to what the output buffers hold
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     int tile, head;
     if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
     int g, ti;
-    find_tile<BM>(a.tab, tile, g, ti);
+    find_tile<BM>(a.tab, a.n_groups, tile, g, ti);
     if (g < 0) return;
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     } else if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
     // key tiles in ascending order: the first prompt tile is seen by every row (most work)
     int g, ti;
-    find_tile<BNK>(a.tab, tile, g, ti);
+    find_tile<BNK>(a.tab, a.n_groups, tile, g, ti);
     const int s0 = ti * BNK;
     if (g < 0) return;
     const GroupDesc gd = load_group(a.tab, g);
@@ -709,7 +709,7 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v; a.d_o = (const __bf16*)p.d_o;
     a.lse = p.lse; a.D = p.Dbuf; a.L2 = p.Dbuf + (int64_t)p.Hq * p.total_tokens;
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;
-    a.tab = p.tab; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
+    a.tab = p.tab; a.n_groups = p.n_groups; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
     a.resp_only = p.resp_only; a.accumulate = p.accumulate;
     if (p.stages & STAGE_DQ) {
         constexpr int NWQ = 8;

@@ -113,10 +113,10 @@ __device__ __forceinline__ int find_group_of_token(const int* __restrict__ tab, 
 // tile number lies past the last group.  Bisection on the group entries' running tile counts,
 // so a batch of many small groups costs log2(n_groups) dependent scalar loads per workgroup.
 template <int BT>
-__device__ __forceinline__ void find_tile(const int* __restrict__ tab, int tile, int& g_out, int& idx_out) {
+__device__ __forceinline__ void find_tile(const int* __restrict__ tab, int n_groups, int tile, int& g_out, int& idx_out) {
     static_assert(BT == 256 || BT == 128, "the table carries running tile counts for 256 and 128 only");
     constexpr int W = BT == 256 ? TAB_TILES256 : TAB_TILES128;
-    int lo = 0, hi = tab[0];
+    int lo = 0, hi = n_groups;         // passed in (a kernel argument): one load less at the head of the chain
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (tab[TAB_HEADER + TAB_GROUP_WORDS * mid + W] <= tile) lo = mid; else hi = mid;

@@ -30,7 +30,7 @@ struct FwdArgs {
     __bf16* o[MAX_SETS]; float* lse[MAX_SETS];
     int blocks_per_set;
     const int* tab;
-    int n_tiles, Hq, Hkv;
+    int n_tiles, n_groups, Hq, Hkv;
     float c;        // softmax_scale * log2(e)
     int naive;
     int resp_only;  // compute and write response rows only
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     int tile, head;
     if (!decode_item(blockIdx.x - set * a.blocks_per_set, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
     int g, ti;
-    find_tile<BM>(a.tab, tile, g, ti);
+    find_tile<BM>(a.tab, a.n_groups, tile, g, ti);
     if (g < 0) return;
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;
@@ -432,7 +432,7 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
         a.v[i] = (const __bf16*)(multi ? p.vs[i] : p.v);
         a.o[i] = (__bf16*)(multi ? p.os[i] : p.o_out); a.lse[i] = multi ? p.lses[i] : p.lse_out;
     }
-    a.tab = p.tab;
+    a.tab = p.tab; a.n_groups = p.n_groups;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive; a.resp_only = p.resp_only;
     a.o_lo = n_sets == 1 ? (__bf16*)p.o_lo_out : nullptr;
     a.n_tiles = count_tiles(p, 256);
