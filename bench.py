@@ -77,7 +77,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--naive", action="store_true", help="also time the naive packed-causal forward")
@@ -165,6 +165,10 @@ def main():
     stage_ms = {}
     for si, name in enumerate(stage_names):
         stage_ms[name] = sum(evs[i][si].elapsed_time(evs[i][si + 1]) for i in range(args.steps)) / args.steps
+    # per-step GPU time (sum of the stage event intervals of that step): median and minimum over the steps
+    per_step = sorted(sum(evs[i][si].elapsed_time(evs[i][si + 1]) for si in range(len(stage_names)))
+                      for i in range(args.steps))
+    step_median = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
     if flush is not None:
         ms_per_step = sum(stage_ms.values())
 
@@ -187,6 +191,7 @@ def main():
         "fwd": {"ms": round(stage_ms["fwd"], 4), "tflops": round(fwd_tf, 2),
                 "pct_peak": round(100.0 * fwd_tf / PEAK_BF16_TFLOPS, 2)},
         "stage_ms": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
+        "step_gpu_ms": {"median": round(step_median, 4), "min": round(per_step[0], 4), "max": round(per_step[-1], 4)},
     }
     if flush is not None:
         out["cold_cache"] = True
