@@ -44,3 +44,22 @@ def test_random_packing_fwd_bwd(seed):
     gate("dQ " + desc, to64(dq), rdq, w.dtype)
     gate("dK " + desc, to64(dk), rdk, w.dtype)
     gate("dV " + desc, to64(dv), rdv, w.dtype)
+
+
+@pytest.mark.parametrize("heads", [(6, 3), (12, 12), (10, 5), (48, 24)])
+def test_kv_head_counts_that_neither_divide_nor_are_a_multiple_of_8(heads):
+    """Such head counts take the plain block -> (tile, head) mapping instead of the XCD-aware ones."""
+    w = random_workload(3)
+    w = W.Workload(f"heads{heads}", w.groups, heads[0], heads[1], 128, torch.bfloat16, 411)
+    t = W.make_tensors(w)
+    pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
+    q, k, v, d_o = t.q.cuda(), t.k.cuda(), t.v.cuda(), t.d_o.cuda()
+    o, lse = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, sc)
+    dq, dk, dv = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc)
+    torch.cuda.synchronize()
+    rdq, rdk, rdv, ro, rlse = oracle_bwd(w, t)
+    gate("O", to64(o), ro, w.dtype)
+    gate_lse(to64(lse), rlse, w.dtype)
+    gate("dQ", to64(dq), rdq, w.dtype)
+    gate("dK", to64(dk), rdk, w.dtype)
+    gate("dV", to64(dv), rdv, w.dtype)
