@@ -82,3 +82,45 @@ def test_tensors_beyond_4_gib_sampled_groups():
         ref = rope_oracle.rope_rotate(to64(qg), rope_oracle.positions(g.prompt_len, g.resp_lens), 1.0e6)
         err = np.abs(to64(qr[sl]) - ref)
         assert float(err.max()) <= 2.0 ** -7 * max(1.0, float(np.abs(ref).max())), (gi, float(err.max()))
+
+
+def test_one_group_of_two_million_tokens_sampled_responses():
+    """One group: a 64-token prompt and 22 000 short ragged responses, 2.3e6 tokens, 8 q = 8 kv heads, so
+    that inside the group a key/value tile (and a query tile of the dkdv pass) lies more than 2^32 bytes
+    past the group's first row.  By the method's defining property the rows of response i (and the prompt
+    rows) equal plain causal attention over [prompt | resp_i]; the oracle on that small problem is the
+    expectation for O, LSE and dQ of those rows and for dK, dV of the response's own keys (no other row
+    sees them).  The prompt's dK/dV sum over all 22 000 responses and are not checked here."""
+    Lp, G, H, d = 64, 22000, 8, 128
+    lens = W.ragged_lengths(9100, G, 90, 120)
+    w = W.Workload("two_million", [W.Group(Lp, lens)], H, H, d, torch.bfloat16, 9100)
+    T = w.total_tokens
+    assert T * H * d * 2 > 2 ** 32 + 2 ** 28
+    t = W.make_tensors_on_device(w, torch.device("cuda:0"))
+    pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
+    o, lse = B.sp_attn_fwd_batched(t.q, t.k, t.v, pl, Gs, rl, sc)
+    dq, dk, dv = B.sp_attn_bwd_batched(t.q, t.k, t.v, o, lse, t.d_o, pl, Gs, rl, sc)
+    torch.cuda.synchronize()
+    for name, x in (("o", o), ("lse", lse), ("dq", dq), ("dk", dk), ("dv", dv)):
+        assert bool(torch.isfinite(x).all()), name
+
+    off = np.concatenate([[Lp], Lp + np.cumsum(lens)])
+    cross = 2 ** 32 // (H * d * 2)                       # token whose row starts 2^32 bytes into q / k
+    i_cross = int(np.searchsorted(off, cross, side="right")) - 1
+    picked = sorted({0, 1, G // 2, i_cross - 1, i_cross, i_cross + 1, G - 1})
+    assert off[i_cross] <= cross < off[i_cross + 1] and i_cross + 1 < G
+    for i in picked:
+        a, b = int(off[i]), int(off[i + 1])
+        idx = torch.cat([torch.arange(0, Lp), torch.arange(a, b)]).cuda()
+        sub = [x[idx].cpu() for x in (t.q, t.k, t.v, t.d_o)]
+        rdq, rdk, rdv, ro, rlse = orc.sp_attn_bwd(*sub, Lp, [b - a], sc)
+        rows = slice(Lp, Lp + b - a)                     # the response's rows inside the small problem
+        print(i, gate(f"O[resp {i}]", to64(o[a:b]), ro[rows], w.dtype))
+        gate_lse(to64(lse[:, a:b]), rlse[:, rows], w.dtype)
+        print(i, gate(f"dQ[resp {i}]", to64(dq[a:b]), rdq[rows], w.dtype))
+        print(i, gate(f"dK[resp {i}]", to64(dk[a:b]), rdk[rows], w.dtype))
+        print(i, gate(f"dV[resp {i}]", to64(dv[a:b]), rdv[rows], w.dtype))
+        if i == picked[0]:                               # prompt rows see only the prompt
+            gate("O[prompt]", to64(o[:Lp]), ro[:Lp], w.dtype)
+            gate_lse(to64(lse[:, :Lp]), rlse[:, :Lp], w.dtype)
+            gate("dQ[prompt]", to64(dq[:Lp]), rdq[:Lp], w.dtype)
