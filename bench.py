@@ -44,8 +44,9 @@ def parse_traffic(workload: str, kernel: str):
 
 def cpu_baseline(w, t, target_seconds=12.0):
     """Time the fp64 oracle (as it stands) on whole q heads of the workload's first group:
-    forward and backward over all rows of each head, one head at a time until about
-    `target_seconds` of CPU work has been done.  Useful FLOPs per head = 14 * d * pairs."""
+    forward and backward (forward only for a forward-only workload) over all rows of each head, one
+    head at a time until about `target_seconds` of CPU work has been done.  Useful FLOPs per head =
+    14 * d * pairs (4 * d * pairs forward only)."""
     import numpy as np
     from oracle import sp_attn_oracle as orc
     from paper_2511_18871_amd import workloads as W
@@ -58,17 +59,21 @@ def cpu_baseline(w, t, target_seconds=12.0):
     n = g.total
     sl = slice(0, n)
     rep = w.n_q_heads // w.n_kv_heads
-    d_o = t.d_o if t.d_o is not None else t.q      # forward-only workloads: any upstream gradient
     heads, dt = 0, 0.0
     while heads < w.n_q_heads and dt < target_seconds:
         t0 = time.perf_counter()
-        orc.sp_attn_bwd(t.q[sl], t.k[sl], t.v[sl], d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale,
-                        kv_heads=[heads // rep], q_heads=[heads], row_block=1024)
+        if w.backward:      # the oracle's backward recomputes the forward: 4*d + 10*d FLOPs per pair
+            orc.sp_attn_bwd(t.q[sl], t.k[sl], t.v[sl], t.d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale,
+                            kv_heads=[heads // rep], q_heads=[heads], row_block=1024)
+        else:
+            orc.sp_attn_fwd(t.q[sl], t.k[sl], t.v[sl], g.prompt_len, g.resp_lens, w.softmax_scale,
+                            heads=[heads], row_block=1024)
         dt += time.perf_counter() - t0
         heads += 1
-    flops = 14.0 * w.head_dim * W.allowed_pairs(g) * heads
+    flops = (14.0 if w.backward else 4.0) * w.head_dim * W.allowed_pairs(g) * heads
+    passes = "forward+backward" if w.backward else "forward"
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"q heads 0..{heads - 1} of {w.n_q_heads}, all {n} rows of group 0, forward+backward in "
+            "sample": f"q heads 0..{heads - 1} of {w.n_q_heads}, all {n} rows of group 0, {passes} in "
                       f"fp64, {dt:.1f} s",
             "seconds": dt}
 
