@@ -336,3 +336,23 @@ def test_micro_batches_sharing_a_prompt_accumulate_to_the_full_batch_gradient():
     assert np.allclose(pdq, dq[:Lp], atol=1e-12)
     assert np.allclose(dk_p + pdk, dk[:Lp], atol=1e-12)
     assert np.allclose(dv_p + pdv, dv[:Lp], atol=1e-12)
+
+
+def test_pair_count_against_the_cost_ratio_of_eq5():
+    """Eq. 5 of Section 4.3 prices the shared mask at (Lp^2 + K Lr (Lp + Lr)) / (K (Lp + Lr)^2) of K
+    per-sample runs, counting squares where a causal mask has triangles.  With triangles on both
+    sides the rectangle term K Lr Lp weighs twice as much, so the exact ratio of the oracle's mask
+    to K causal masks over Lp + Lr tokens is the printed ratio + Lr Lp / (Lp + Lr)^2, up to the
+    diagonals (O(1 / (Lp + Lr))); and it tends to 1 / K for Lp >> Lr as the section states."""
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "cost_ratio_eq5.txt")) if ln.strip() and ln[0] != "#"]
+    assert len(rows) == 3
+    for lp, lr, k, num, den, rho in rows:
+        lp, lr, k, num, den, rho = int(lp), int(lr), int(k), int(num), int(den), float(rho)
+        assert abs(num / den - rho) < 1e-6                       # the fixture is self-consistent
+        n = lp + lr
+        shared = int(orc.build_mask(lp, [lr] * k).sum())
+        per_sample = k * int(np.tril(np.ones((n, n), dtype=bool)).sum())
+        exact = shared / per_sample
+        assert abs(exact - (rho + lr * lp / n ** 2)) < 2.0 / n, (lp, lr, k, exact, rho)
+    lp, lr, k = 2000, 2, 4
+    assert abs(int(orc.build_mask(lp, [lr] * k).sum()) / (k * (lp + lr) * (lp + lr + 1) // 2) - 1.0 / k) < 2e-3
