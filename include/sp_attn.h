@@ -121,7 +121,9 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v,
 /* The backward runs in three stages that a caller may enqueue separately, e.g. to time
  * them or to overlap the two gradient passes on two streams:
  *   SP_BWD_STAGE_ROWSUM  D[h, t] = sum_j d_o[t,h,j] * o[t,h,j] and lse * log2(e) -> workspace
- *                        (needs o, d_o, lse)
+ *                        (needs o, d_o, lse; on the bf16 path also q, k, v: rows that see at
+ *                        most 64 keys get D from its definition sum_s P*dP instead, because
+ *                        the rounding of o weighs most on dq where a row has few keys)
  *   SP_BWD_STAGE_DQ      dq      (needs D in the same workspace; o unused).  On the bf16 path it
  *                        also replaces D in the workspace by sum_s P*dP, the same quantity
  *                        evaluated in fp32 without the bf16 rounding of o.

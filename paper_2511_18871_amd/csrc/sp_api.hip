@@ -49,6 +49,7 @@ struct Layout {
     int64_t total_tokens = 0;
     int64_t total_responses = 0;
     int max_group_tokens = 0;
+    int min_prompt_len = 0x7fffffff;
 };
 
 sp_status build_table(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
@@ -69,6 +70,7 @@ sp_status build_table(int32_t n_groups, const int32_t* prompt_lens, const int32_
     size_t roff = (size_t)sp::TAB_HEADER + (size_t)sp::TAB_GROUP_WORDS * n_groups;
     for (int g = 0; g < n_groups; ++g) {
         if (prompt_lens[g] < 0) return fail(SP_ERR_INVALID_ARG, "group %d: prompt_len is negative", g);
+        if (prompt_lens[g] < L.min_prompt_len) L.min_prompt_len = prompt_lens[g];
         int64_t tg = prompt_lens[g];
         int32_t* e = &L.words[sp::TAB_HEADER + sp::TAB_GROUP_WORDS * g];
         e[0] = (int32_t)tok; e[1] = prompt_lens[g]; e[3] = (int32_t)roff; e[4] = Gs[g];
@@ -135,6 +137,7 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.dkdv_partial = (bwd && dtype == SP_BF16 && sp::dkdv_head_split(L.total_tokens, n_groups, Hq, Hkv))
                          ? (float*)((char*)p.Dbuf + align256((size_t)Hq * (size_t)L.total_tokens * 8)) : nullptr;
     p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
+    p.total_responses = L.total_responses; p.min_prompt_len = L.min_prompt_len;
     p.Hq = Hq; p.Hkv = Hkv; p.head_dim = d; p.scale = scale;
     p.naive = schedule == SP_SCHED_NAIVE_CAUSAL;
     p.stages = stages;
@@ -275,6 +278,7 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
     sp::Problem p{};
     p.tab = (const int*)workspace;
     p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
+    p.total_responses = L.total_responses; p.min_prompt_len = L.min_prompt_len;
     p.Hq = n_q_heads; p.Hkv = n_kv_heads; p.head_dim = head_dim; p.scale = softmax_scale;
     p.host_group_tokens = L.group_tokens.data();
     hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);

@@ -22,6 +22,8 @@ struct Problem {
     float* Dbuf;                                          // [Hq, T_total] rowsum(dO*O) (device)
     int n_groups;
     int64_t total_tokens;
+    int64_t total_responses;
+    int min_prompt_len;                                   // shortest prompt of the batch
     int max_group_tokens;
     int Hq, Hkv, head_dim;
     float scale;
