@@ -274,6 +274,20 @@ sp_status sp_attn_grpo_loss(const float* logp, const float* logp_old, const floa
                             const int32_t* Gs, const int32_t* resp_lens_flat,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* The segment table that every call builds from its host arrays and hands to its kernels (Section
+ * 4.3, packing and mask: the table is the only form in which they reach the device).  Written to
+ * HOST memory `words` (capacity in int32 words); *n_words receives the count needed, also when
+ * the capacity is too small (then SP_ERR_WORKSPACE and nothing is written) or words is NULL.
+ * Layout, all int32:
+ *   [0] n_groups  [1] total tokens  [2] table words  [3] 0
+ *   group g at 4 + 8 g: { first packed token, prompt_len, tokens T_g, index of its offsets, G,
+ *                         256-row tiles in earlier groups, 128-key tiles in earlier groups, 0 }
+ *   then per group G + 1 group-local offsets: prompt_len, ends of responses 1 .. G (the last = T_g).
+ * No device work; for tools and tests.  Errors as the host checks of sp_attn_fwd_batched. */
+sp_status sp_attn_segment_table(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
+                                const int32_t* resp_lens_flat, int32_t* words, size_t capacity,
+                                size_t* n_words);
+
 /* Text of the most recent error on the calling thread ("" if none).  The pointer
  * refers to thread-local static storage; the caller must not free it. */
 const char* sp_attn_last_error(void);

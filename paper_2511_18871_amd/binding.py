@@ -24,7 +24,7 @@ SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
            "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
            "sp_attn_loss_workspace_bytes", "sp_attn_logprob_fwd", "sp_attn_logprob_bwd", "sp_attn_grpo_loss",
-           "sp_attn_last_error", "sp_attn_version")
+           "sp_attn_segment_table", "sp_attn_last_error", "sp_attn_version")
 
 _lib = None
 
@@ -82,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_grpo_loss.argtypes = [vp, vp, vp, vp, f32, f32, f32, vp, vp, i32, ip, ip, ip, vp, sz, vp]
     lib.sp_attn_rope.restype = ctypes.c_int
     lib.sp_attn_rope.argtypes = [vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_segment_table.restype = ctypes.c_int
+    lib.sp_attn_segment_table.argtypes = [i32, ip, ip, ip, ip, sz, ctypes.POINTER(sz)]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
     lib.sp_attn_last_error.argtypes = []
     lib.sp_attn_version.restype = ctypes.c_char_p
@@ -93,6 +95,19 @@ def load_library() -> ctypes.CDLL:
 def _check(status: int) -> None:
     if status != SP_OK:
         raise SpAttnError(status, load_library().sp_attn_last_error().decode())
+
+
+def sp_attn_segment_table(prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int]) -> list:
+    """The segment table (list of ints) that a call with these host arrays hands to its kernels."""
+    lib = load_library()
+    n = ctypes.c_size_t(0)
+    args = (len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat))
+    st = lib.sp_attn_segment_table(*args, None, 0, ctypes.byref(n))
+    if st != SP_ERR_WORKSPACE:
+        _check(st)
+    buf = (ctypes.c_int32 * n.value)()
+    _check(lib.sp_attn_segment_table(*args, buf, n.value, ctypes.byref(n)))
+    return list(buf)
 
 
 def _i32(xs: Sequence[int]):

@@ -405,6 +405,21 @@ sp_status sp_attn_grpo_loss(const float* logp, const float* logp_old, const floa
     return SP_OK;
 }
 
+sp_status sp_attn_segment_table(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
+                                const int32_t* resp_lens_flat, int32_t* words, size_t capacity,
+                                size_t* n_words) {
+    g_err[0] = 0;
+    if (!n_words) return fail(SP_ERR_INVALID_ARG, "n_words is NULL");
+    Layout L;
+    sp_status st = build_table(n_groups, prompt_lens, Gs, resp_lens_flat, L);
+    if (st != SP_OK) return st;
+    *n_words = L.words.size();
+    if (!words || capacity < L.words.size())
+        return fail(SP_ERR_WORKSPACE, "segment table needs %zu words, capacity is %zu", L.words.size(), words ? capacity : (size_t)0);
+    for (size_t i = 0; i < L.words.size(); ++i) words[i] = L.words[i];
+    return SP_OK;
+}
+
 const char* sp_attn_last_error(void) { return g_err; }
 const char* sp_attn_version(void) { return "0.1"; }
 

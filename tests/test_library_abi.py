@@ -151,3 +151,53 @@ def test_loss_calls_reject_bad_arguments(lib):
     assert q(el=1.0) == B.SP_ERR_INVALID_ARG and q(el=-0.1) == B.SP_ERR_INVALID_ARG
     assert q(eh=float("inf")) == B.SP_ERR_INVALID_ARG and q(beta=float("nan")) == B.SP_ERR_INVALID_ARG
     assert q(ws=None) == B.SP_ERR_WORKSPACE
+
+
+def test_segment_table_contents(lib):
+    """The host logic that turns (prompt_lens, Gs, resp_lens) into the table the kernels read: token
+    bases, per-group offsets and the running tile counts that the tile -> group bisection relies on."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        ng = int(rng.integers(1, 30))
+        pl = [int(x) for x in rng.integers(0, 700, ng)]
+        Gs = [int(x) for x in rng.integers(0, 6, ng)]
+        rl = [int(x) for g in Gs for x in rng.integers(0, 300, g)]
+        if trial == 0:
+            pl, Gs, rl = [0, 5], [2, 0], [0, 256]          # a zero-length response, a group with no response
+        for g in range(ng if trial else 2):                # every group needs at least one token
+            if pl[g] + sum(rl[sum(Gs[:g]):sum(Gs[:g + 1])]) == 0:
+                pl[g] = 1
+        ng = len(pl)
+        tab = B.sp_attn_segment_table(pl, Gs, rl)
+        totals = [pl[g] + sum(rl[sum(Gs[:g]):sum(Gs[:g + 1])]) for g in range(ng)]
+        assert tab[0] == ng and tab[1] == sum(totals) and tab[2] == len(tab) == 4 + 8 * ng + sum(Gs) + ng and tab[3] == 0
+        next_off, tok, t256, t128, r = 4 + 8 * ng, 0, 0, 0, 0
+        for g in range(ng):
+            e = tab[4 + 8 * g: 12 + 8 * g]
+            assert e == [tok, pl[g], totals[g], next_off, Gs[g], t256, t128, 0], (trial, g, e)
+            offs = tab[next_off: next_off + Gs[g] + 1]
+            want = [pl[g]]
+            for i in range(Gs[g]):
+                want.append(want[-1] + rl[r + i])
+            assert offs == want and offs[-1] == totals[g]
+            r += Gs[g]
+            next_off += Gs[g] + 1
+            tok += totals[g]
+            t256 += -(-totals[g] // 256)
+            t128 += -(-totals[g] // 128)
+        assert next_off == len(tab)
+
+
+def test_segment_table_errors(lib):
+    n = ctypes.c_size_t(0)
+    i32 = lambda xs: (ctypes.c_int32 * max(1, len(xs)))(*xs)
+    buf = (ctypes.c_int32 * 4)()
+    # too small a buffer: the needed size is still reported
+    assert lib.sp_attn_segment_table(1, i32([10]), i32([2]), i32([3, 4]), buf, 4, ctypes.byref(n)) == B.SP_ERR_WORKSPACE
+    assert n.value == 4 + 8 + 3
+    assert lib.sp_attn_segment_table(1, i32([10]), i32([2]), i32([3, -4]), None, 0, ctypes.byref(n)) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_segment_table(1, i32([0]), i32([1]), i32([0]), None, 0, ctypes.byref(n)) == B.SP_ERR_INVALID_ARG
+    assert b"empty" in lib.sp_attn_last_error()
+    assert lib.sp_attn_segment_table(0, i32([]), i32([]), i32([]), None, 0, ctypes.byref(n)) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_segment_table(1, i32([10]), i32([0]), None, None, 0, None) == B.SP_ERR_INVALID_ARG
