@@ -161,8 +161,9 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
  *                             in the output dtype) instead of overwritten, so the prompt's dk/dv
  *                             can be summed over micro-batches in place (each accumulation
  *                             rounds the running sum to the output dtype once more).
- *                             With SP_FLAG_RESPONSE_ROWS the backward reads o and lse on response
- *                             rows only; their prompt rows may hold anything.
+ *                             With SP_FLAG_RESPONSE_ROWS the backward uses o and lse on response
+ *                             rows only; their prompt rows may hold anything (the buffers are
+ *                             still full-size: prompt rows may be read and discarded).
  * The prompt rows' own backward (plain causal attention over the prompt, with the upstream
  * gradient of the prompt rows summed over the micro-batches) is an ordinary call with G = 0.
  * The _ex entry points are sp_attn_fwd_batched / sp_attn_bwd_batched_stages with a flags word and
