@@ -28,8 +28,12 @@
  *     never allocates, frees or synchronises; work is enqueued on `stream`
  *     (a hipStream_t passed as void*, NULL = the default stream) and the call
  *     returns at once.  Outputs are overwritten, inputs are never modified.
- *   - Every call returns sp_status.  On any error nothing has been enqueued and
- *     sp_attn_last_error() describes the reason.
+ *   - Every call returns sp_status and sp_attn_last_error() describes a failure.  Arguments,
+ *     geometry and workspace are checked before anything is enqueued: on SP_ERR_INVALID_ARG,
+ *     SP_ERR_UNSUPPORTED and SP_ERR_WORKSPACE no work has been enqueued and no memory is touched.
+ *     SP_ERR_DEVICE means the HIP runtime rejected one of the call's launches; launches of the
+ *     same call that preceded it (the segment-table upload into the workspace, earlier stages)
+ *     stay enqueued, so the workspace and the outputs are then undefined.
  */
 #ifndef SP_ATTN_H
 #define SP_ATTN_H

@@ -12,8 +12,8 @@ What it computes.
   on response rows and 0 on prompt rows.
 
 * The GRPO objective over those log-probabilities (Section 2: J = 1/(NG) sum_k (L_k - beta D_KL^k),
-  L_k "the PPO-style clipped advantage term", D_KL^k "the KL penalty between the policy and
-  reference model"; Appendix hyper-parameters eps_low = eps_high = 0.2, beta = 0.02).  The paper
+  L_k the clipped surrogate term of response k, D_KL^k its policy-versus-reference KL estimate;
+  Appendix hyper-parameters eps_low = eps_high = 0.2, beta = 0.02).  The paper
   does not print L_k and D_KL^k; the reading taken is the GRPO form its training recipe names:
       r_t   = exp(logp_t - logp_old_t)
       L_k   = 1/|o_k| sum_t min(r_t A_k, clip(r_t, 1 - eps_low, 1 + eps_high) A_k)

@@ -705,7 +705,7 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
         e = launch_rowsum(p, false, s);
         if (e != hipSuccess) return e;
     }
-    BwdArgs a;
+    BwdArgs a{};
     a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v; a.d_o = (const __bf16*)p.d_o;
     a.lse = p.lse; a.D = p.Dbuf; a.L2 = p.Dbuf + (int64_t)p.Hq * p.total_tokens;
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;

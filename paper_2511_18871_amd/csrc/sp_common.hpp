@@ -233,8 +233,10 @@ __device__ __forceinline__ float pair_sum(float x) {
 // Written as inline assembly so that the compiler does not place a conservative
 // "wait for all global loads" in front of every later LDS read; the kernels order the
 // copy against its readers themselves with wait_vm0() followed by a workgroup barrier.
-// M0 (the LDS base of the copy) is overwritten; gfx9 LDS instructions do not read M0 and
-// nothing else in these kernels keeps a value in it.
+// M0 (the LDS base of the copy) is overwritten.  It cannot be named as a clobber: the compiler
+// treats M0 as a reserved register (it rejects the clobber as undefined behaviour) and writes it
+// itself immediately before each of its own uses, never keeping a value in it across statements;
+// gfx9 LDS instructions do not read M0 and nothing else in these kernels uses it.
 __device__ __forceinline__ void async_copy16(const void* gptr, char* lds_base) {
     const unsigned lds_addr = __builtin_amdgcn_readfirstlane(
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);

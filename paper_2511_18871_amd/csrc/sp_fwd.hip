@@ -23,6 +23,7 @@ namespace {
 constexpr int BN = 64;                 // keys per LDS tile
 constexpr float P_LIMIT = 16384.0f;     // bound on a lane's per-tile sum of exponentials (2^14)
 constexpr int TILE_BYTES = BN * 256;   // 64 rows x 128 bf16
+constexpr float M_NONE = -1.0e30f;     // reference point of a row that has not seen a key yet (finite on purpose)
 
 struct FwdArgs {
     // one entry per tensor set; the sets share the packing, the schedule and the launch
@@ -329,9 +330,15 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         lsr += tsr;
     };
 
-    // zero-fill the V buffer that the first step multiplies against P = 0 (it stands for V(-1))
-    for (int i = tid; i < TILE_BYTES / 16; i += 512)
-        reinterpret_cast<i32x4*>(ldsVb[3])[i] = i32x4{0, 0, 0, 0};
+    // Zero-fill every V buffer that is multiplied against P = 0 before a copy has filled it: buffer 3
+    // stands for V(-1) in the first step, and a key loop of fewer than three tiles is still padded to
+    // four steps, whose V(1), V(2) are never copied.  LDS keeps what earlier workgroups left there (bit
+    // patterns that may read as inf or NaN), and 0 * NaN would reach O.
+#pragma unroll
+    for (int b = 1; b < 4; ++b)
+        if (b == 3 || total <= b)
+            for (int i = tid; i < TILE_BYTES / 16; i += 512)
+                reinterpret_cast<i32x4*>(ldsVb[b])[i] = i32x4{0, 0, 0, 0};
     issue(kbase_s, m0K[0], 0);
     issue(kbase_s, m0K[1], 1);
     issue(kbase_s, m0K[2], 2);
@@ -345,7 +352,12 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 #pragma unroll
         for (int e = 1; e < 32; ++e) mx = fmaxf(mx, sA[e >> 4][e & 15]);
         mx = pair_max(mx);
-        m = (mx == -INFINITY) ? 0.f : mx;      // rows that see nothing in this tile start from 0
+        // A row that sees nothing in this tile (possible only without a prompt: a later response's
+        // rows against the first response's keys) starts from a finite sentinel far below any score:
+        // the first tile in which it does see a key then overflows the after-check and takes that
+        // tile's exact maximum.  (Starting from 0 would let a row whose scores all lie below about
+        // -126 / log2(e) underflow to a zero sum.)
+        m = (mx == -INFINITY) ? M_NONE : mx;
     }
     // Two steps per workgroup barrier: with four K and four V buffers the tiles of the next two
     // steps are copied while these two run.  At the barrier before steps j, j+1 (j even) the tiles

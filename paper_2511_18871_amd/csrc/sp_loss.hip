@@ -122,14 +122,19 @@ __global__ __launch_bounds__(256) void grpo_kernel(const float* __restrict__ log
     const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int l = threadIdx.x & 63;
     if (k >= n_resp) return;
-    int grp = 0, first = 0;                              // group that holds response k
-    for (const int ng = tab[0]; grp < ng; ++grp) {
-        const int G = tab[TAB_HEADER + TAB_GROUP_WORDS * grp + 4];
-        if (k < first + G) break;
-        first += G;
+    // Group that holds response k.  Group g's response offsets start at table word e[3] = base + R_g + g,
+    // with base the first offset word and R_g the responses in earlier groups, so R_g is read off the
+    // group entries and the group is the last one with R_g <= k: a bisection (responses of empty groups
+    // never match, since R_g of the next group is the same).
+    const int ng = tab[0];
+    const int base = TAB_HEADER + TAB_GROUP_WORDS * ng;
+    int lo = 0, hi = ng;                                 // invariant: R_lo <= k, (hi == ng or R_hi > k)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tab[TAB_HEADER + TAB_GROUP_WORDS * mid + 3] - base - mid <= k) lo = mid; else hi = mid;
     }
-    const GroupDesc gd = load_group(tab, grp);
-    const int i = k - first;
+    const GroupDesc gd = load_group(tab, lo);
+    const int i = k - (tab[TAB_HEADER + TAB_GROUP_WORDS * lo + 3] - base - lo);
     const int b = gd.roff[i], e = gd.roff[i + 1];       // group-local token range of the response
     const float a = adv[k];
     const float inv_len = e > b ? 1.0f / (float)(e - b) : 0.f;
