@@ -85,7 +85,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
-    ap.add_argument("--naive", action="store_true", help="also time the naive packed-causal forward")
+    ap.add_argument("--no-naive", action="store_true", help="skip the naive packed-causal forward baseline")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the MFMA-only ceiling loops")
     ap.add_argument("--inputs", choices=["random", "zeros"], default="random",
                     help="zeros: run the same kernels on all-zero tensors (a power diagnostic: the instruction\n"
                          "stream is identical, only operand toggling differs; not the metric)")
@@ -220,7 +221,9 @@ def main():
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(fwd_tf / PEAK_BF16_TFLOPS, 4),
                            "traffic": parse_traffic(w.name, "fwd_kernel")}
 
-    if args.naive:
+    if w.dtype == torch.bfloat16 and not args.no_naive:
+        # naive packed-causal baseline: the same kernel visiting every tile at or below the diagonal of the
+        # packed sequence with an element-wise mask; useful FLOPs in the numerator, like the product path
         evn = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, scale, schedule=B.SP_SCHED_NAIVE_CAUSAL, o=o, lse=lse, workspace=ws)
         evn[0].record()
@@ -230,7 +233,41 @@ def main():
         evn[1].record()
         torch.cuda.synchronize()
         nms = evn[0].elapsed_time(evn[1]) / 5
-        out["naive_fwd"] = {"ms": round(nms, 4), "useful_tflops": round(fwd_flops / (nms * 1e-3) / 1e12, 2)}
+        out["naive_fwd"] = {"ms": round(nms, 4), "useful_tflops": round(fwd_flops / (nms * 1e-3) / 1e12, 2),
+                            "speedup_of_shared_schedule": round(nms / stage_ms["fwd"], 3)}
+
+    if w.dtype == torch.bfloat16 and not args.no_ceiling:
+        # what a loop of nothing but bf16 MFMAs sustains on this machine, per LDS operands read per MFMA and per
+        # operand values (N(0,1) like the workload's tensors; all-ones for the same loop at low power)
+        gen = torch.Generator(device="cpu").manual_seed(7)
+        n_op = 8 * 512 * 8
+        rnd = [torch.randn(n_op, generator=gen).to(torch.bfloat16).to(dev) for _ in range(2)]
+        one = [torch.ones(n_op, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+        sink = torch.empty(512, dtype=torch.float32, device=dev)
+        ceil = {}
+        for data_name, (xa, xb) in (("random", rnd), ("ones", one)):
+            for n_lds in (0, 1, 2):
+                B.sp_attn_mfma_ceiling(n_lds, xa, xb, 200, sink)
+                evc = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                evc[0].record()
+                fl = B.sp_attn_mfma_ceiling(n_lds, xa, xb, 6000, sink)      # about 3 ms: long enough to settle the clock
+                evc[1].record()
+                torch.cuda.synchronize()
+                ceil[f"{data_name}_lds{n_lds}"] = round(fl / (evc[0].elapsed_time(evc[1]) * 1e-3) / 1e12, 1)
+        out["mfma_ceiling"] = {"unit": "TFLOP/s", **ceil,
+                               "note": "bf16 32x32x16 MFMA loop, 8 waves per CU; ldsN = operands read from LDS per MFMA"}
+        # the attention kernels against the ceiling of their own operand mix on random data
+        out["fwd"]["pct_of_measured_ceiling"] = round(100.0 * fwd_tf / ceil["random_lds1"], 1)
+        if do_bwd:
+            # executed rates: the dq pass runs 6*d and the dkdv pass 8*d FLOPs per allowed pair and q head
+            pairs_hq = fwd_flops / (4.0 * d)
+            dq_exec = 6.0 * d * pairs_hq / (stage_ms["bwd_dq"] * 1e-3) / 1e12
+            dkdv_exec = 8.0 * d * pairs_hq / (stage_ms["bwd_dkdv"] * 1e-3) / 1e12
+            out["bwd"]["dq_executed_tflops"] = round(dq_exec, 1)
+            out["bwd"]["dkdv_executed_tflops"] = round(dkdv_exec, 1)
+            out["bwd"]["dq_pct_of_measured_ceiling"] = round(100.0 * dq_exec / ceil["random_lds1"], 1)
+            out["bwd"]["dkdv_pct_of_measured_ceiling"] = round(
+                100.0 * dkdv_exec / (0.5 * (ceil["random_lds1"] + ceil["random_lds2"])), 1)
 
     if w.n_sets > 1:
         # all weight sets of the workload (policy / old policy / reference) in one launch,

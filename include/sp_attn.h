@@ -150,6 +150,28 @@ sp_status sp_attn_bwd_batched_stages(const void* q, const void* k, const void* v
                                      float softmax_scale, sp_dtype dtype, uint32_t stages,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* sp_attn_bwd_batched for callers that cannot allocate or hand over device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results
+ * (bitwise) as sp_attn_bwd_batched, without the workspace: the segment table, D and the other
+ * intermediates live in an array of SP_STATIC_SCRATCH_BYTES bytes that is part of the library's
+ * device image (every GPU the library is used on holds its own copy until the process ends).  The
+ * call allocates and frees nothing, on the host's HIP side or through any library.
+ *   - A problem whose sp_attn_workspace_bytes(1, ...) exceeds SP_STATIC_SCRATCH_BYTES is rejected with
+ *     SP_ERR_WORKSPACE before anything is enqueued (bf16: about n_q_heads * T_total <= 4e6).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *     streams, or host threads) race on it.  Calls ordered on one stream are safe; every call
+ *     rewrites all it reads, so nothing carries over from one call to the next.
+ *   - Runs on the device that is current at the call; SP_ERR_DEVICE if its address of the array
+ *     cannot be obtained. */
+#define SP_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+sp_status sp_attn_bwd_batched_static(const void* q, const void* k, const void* v,
+                                     const void* o, const float* lse, const void* d_o,
+                                     void* dq, void* dk, void* dv,
+                                     int32_t n_groups, const int32_t* prompt_lens,
+                                     const int32_t* Gs, const int32_t* resp_lens_flat,
+                                     int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                     float softmax_scale, sp_dtype dtype, void* stream);
+
 /* Micro-batches that share a prompt.  When the G responses of a prompt are spread over several
  * micro-batches (the paper's runs share 16 of 32 rollouts per micro-batch), each micro-batch packs
  * [prompt | its responses] and the gradient of the group is the sum over its members (Section 3,
@@ -292,6 +314,19 @@ sp_status sp_attn_grpo_loss(const float* logp, const float* logp_old, const floa
 sp_status sp_attn_segment_table(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
                                 const int32_t* resp_lens_flat, int32_t* words, size_t capacity,
                                 size_t* n_words);
+
+/* Measurement aid (no counterpart in the paper): a loop of nothing but bf16 32x32x16 MFMAs, so that
+ * the attention kernels' rates can be read against what the matrix cores of this chip sustain.
+ *   lds_operands  0: both operands in registers; 1: one operand read from LDS per MFMA (as in the
+ *                 forward and the dq pass); 2: both read from LDS
+ *   a, b          DEVICE, 16-byte aligned, 8 * 512 * 8 bf16 each: the operand values (random values
+ *                 draw the power real data draws; constants do not)
+ *   iters         iterations of 16 MFMAs per wave;  n_blocks  workgroups of 8 waves (256 = one per CU)
+ *   out           DEVICE float[512], overwritten
+ * Executes n_blocks * 8 * iters * 16 * 32768 FLOPs.  Asynchronous on `stream`.
+ * SP_ERR_INVALID_ARG for a NULL/misaligned pointer or a count < 1. */
+sp_status sp_attn_mfma_ceiling(int32_t lds_operands, const void* a, const void* b, int32_t iters,
+                               int32_t n_blocks, float* out, void* stream);
 
 /* Text of the most recent error on the calling thread ("" if none).  The pointer
  * refers to thread-local static storage; the caller must not free it. */

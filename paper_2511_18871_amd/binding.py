@@ -22,9 +22,9 @@ SP_BWD_STAGE_ROWSUM, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2
 SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
-           "sp_attn_bwd_batched", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
+           "sp_attn_bwd_batched", "sp_attn_bwd_batched_static", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
            "sp_attn_loss_workspace_bytes", "sp_attn_logprob_fwd", "sp_attn_logprob_bwd", "sp_attn_grpo_loss",
-           "sp_attn_segment_table", "sp_attn_last_error", "sp_attn_version")
+           "sp_attn_segment_table", "sp_attn_mfma_ceiling", "sp_attn_last_error", "sp_attn_version")
 
 _lib = None
 
@@ -59,6 +59,9 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_bwd_batched.restype = ctypes.c_int
     lib.sp_attn_bwd_batched.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32,
                                         ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_bwd_batched_static.restype = ctypes.c_int
+    lib.sp_attn_bwd_batched_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32, f32,
+                                               ctypes.c_int, vp]
     lib.sp_attn_bwd_batched_stages.restype = ctypes.c_int
     lib.sp_attn_bwd_batched_stages.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ip, ip, ip, i32, i32, i32,
                                                f32, ctypes.c_int, ctypes.c_uint32, vp, sz, vp]
@@ -84,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_rope.argtypes = [vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_segment_table.restype = ctypes.c_int
     lib.sp_attn_segment_table.argtypes = [i32, ip, ip, ip, ip, sz, ctypes.POINTER(sz)]
+    lib.sp_attn_mfma_ceiling.restype = ctypes.c_int
+    lib.sp_attn_mfma_ceiling.argtypes = [i32, vp, vp, i32, i32, vp, vp]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
     lib.sp_attn_last_error.argtypes = []
     lib.sp_attn_version.restype = ctypes.c_char_p
@@ -327,6 +332,28 @@ def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Se
                                    _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
                                    _dtype_code(q), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def sp_attn_mfma_ceiling(lds_operands: int, a, b, iters: int, out, n_blocks: int = 256, stream=None) -> float:
+    """Enqueue the MFMA-only measurement loop; returns the FLOPs the launch executes."""
+    lib = load_library()
+    st = lib.sp_attn_mfma_ceiling(lds_operands, a.data_ptr(), b.data_ptr(), iters, n_blocks, out.data_ptr(),
+                                  _stream_ptr(stream))
+    if st != SP_OK:
+        raise SpAttnError(st, "sp_attn_mfma_ceiling: invalid argument or launch failure")
+    return float(n_blocks) * 8 * iters * 16 * 32768.0
+
+
+def sp_attn_bwd_batched_static(q, k, v, o, lse, d_o, dq, dk, dv, prompt_lens: Sequence[int], Gs: Sequence[int],
+                               resp_lens_flat: Sequence[int], softmax_scale: float, stream=None) -> None:
+    """sp_attn_bwd_batched on the library's built-in device scratch: no workspace, and nothing is
+    allocated (the caller passes every output)."""
+    lib = load_library()
+    T, Hq, d = q.shape
+    _check(lib.sp_attn_bwd_batched_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                          d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                          len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq,
+                                          k.shape[1], d, softmax_scale, _dtype_code(q), _stream_ptr(stream)))
 
 
 def sp_attn_bwd_batched_stages(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],

@@ -4,10 +4,19 @@
 #include "sp_common.hpp"
 #include "sp_launch.hpp"
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <vector>
+
+// Device memory of the entry point that takes no workspace (sp_attn_bwd_batched_static): segment
+// table, D and scaled-LSE planes and, on small problems, the per-q-head dK/dV partial sums.  Every
+// GPU the library runs on holds its own copy of the array at its own address for the life of the
+// process.  In host code the array's NAME is only a handle for hipGetSymbolAddress: kernels are
+// given the per-device address obtained from it, never the name.
+#define SP_STATIC_SCRATCH_BYTES_IMPL ((size_t)32 << 20)
+static __device__ __align__(256) unsigned char scratch[SP_STATIC_SCRATCH_BYTES_IMPL];
 
 namespace {
 
@@ -418,6 +427,46 @@ sp_status sp_attn_segment_table(int32_t n_groups, const int32_t* prompt_lens, co
         return fail(SP_ERR_WORKSPACE, "segment table needs %zu words, capacity is %zu", L.words.size(), words ? capacity : (size_t)0);
     for (size_t i = 0; i < L.words.size(); ++i) words[i] = L.words[i];
     return SP_OK;
+}
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` on each GPU, 0 = not asked yet
+}
+
+sp_status sp_attn_bwd_batched_static(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                     const void* d_o, void* dq, void* dk, void* dv, int32_t n_groups,
+                                     const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                                     int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                                     sp_dtype dtype, void* stream) {
+    static_assert(SP_STATIC_SCRATCH_BYTES_IMPL == SP_STATIC_SCRATCH_BYTES, "header and array disagree");
+    g_err[0] = 0;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(SP_ERR_DEVICE, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(SP_ERR_UNSUPPORTED, "device ordinal %d is outside 0..%d", dev, MAX_DEVICES - 1);
+    void* ws = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ws) {
+        // once per device, with that device current: each GPU has the array at its own address
+        e = hipGetSymbolAddress(&ws, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ws)
+            return fail(SP_ERR_DEVICE, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev].store(ws, std::memory_order_release);
+    }
+    // Everything the kernels read from the scratch is written earlier in the same call (table by the
+    // upload, D / scaled LSE by the rowsum stage, partial sums by the dkdv pass for every key), so
+    // nothing has to be cleared; a problem that needs more than the array is rejected by the
+    // workspace check of the common path before anything is enqueued.
+    sp_status st = run(true, q, k, v, o, lse, d_o, nullptr, nullptr, dq, dk, dv, n_groups, prompt_lens, Gs,
+                       resp_lens_flat, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, SP_SCHED_SHARED,
+                       SP_BWD_STAGE_ALL, 0u, ws, SP_STATIC_SCRATCH_BYTES, stream);
+    if (st == SP_ERR_WORKSPACE) {
+        char msg[sizeof(g_err)];
+        snprintf(msg, sizeof(msg), "%s", g_err);
+        return fail(SP_ERR_WORKSPACE, "problem exceeds the built-in scratch of %zu bytes (use sp_attn_bwd_batched "
+                    "with a workspace): %.300s", (size_t)SP_STATIC_SCRATCH_BYTES, msg);
+    }
+    return st;
 }
 
 const char* sp_attn_last_error(void) { return g_err; }
