@@ -132,7 +132,9 @@ def main():
     o = torch.empty_like(q)
     lse = torch.empty(Hq, T, dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, Hkv, d, code), dtype=torch.uint8, device=dev)
+    # one workspace for the forward and the backward, with room for the forward-to-backward reserve
+    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, Hkv, d, code) + B.reserve_bytes(T, Hq, d, code),
+                     dtype=torch.uint8, device=dev)
     do_bwd = w.backward
 
     stage_names = ["fwd"] + (["bwd_rowsum", "bwd_dq", "bwd_dkdv"] if do_bwd else [])

@@ -28,6 +28,8 @@
  *     never allocates, frees or synchronises; work is enqueued on `stream`
  *     (a hipStream_t passed as void*, NULL = the default stream) and the call
  *     returns at once.  Outputs are overwritten, inputs are never modified.
+ *     A workspace carries nothing from call to call except the optional forward-to-backward
+ *     reserve described at sp_attn_reserve_bytes().
  *   - Every call returns sp_status and sp_attn_last_error() describes a failure.  Arguments,
  *     geometry and workspace are checked before anything is enqueued: on SP_ERR_INVALID_ARG,
  *     SP_ERR_UNSUPPORTED and SP_ERR_WORKSPACE no work has been enqueued and no memory is touched.
@@ -74,6 +76,22 @@ typedef enum { SP_SCHED_SHARED = 0, SP_SCHED_NAIVE_CAUSAL = 1 } sp_schedule;
 size_t sp_attn_workspace_bytes(int is_bwd, int64_t total_tokens, int32_t n_groups,
                                int64_t total_responses, int32_t n_q_heads,
                                int32_t n_kv_heads, int32_t head_dim, sp_dtype dtype);
+
+/* Forward-to-backward reserve (bf16 only; 0 for SP_F32).  The backward starts from
+ * D = rowsum(d_o * o), and o reaches it rounded to bf16; where one key dominates a row, that
+ * rounding is the largest error of dq and dk.  A forward whose workspace has at least
+ *     sp_attn_workspace_bytes(1, ...) + sp_attn_reserve_bytes(...)
+ * bytes also leaves there what the rounding of o dropped (o_fp32 - o, itself in bf16; o is
+ * unchanged), and a backward that is handed THE SAME workspace, not used by any other call in
+ * between, forms D from o plus that residual.  Nothing else changes hands: same arguments, same
+ * outputs.  The reserve is protected by a tag at the head of the workspace, naming the o / lse
+ * pointers and the shape it belongs to; every call of this library rewrites or re-validates the tag
+ * on the device before it writes to a workspace, so a backward that is given a smaller, another,
+ * or a since-reused workspace finds no valid reserve and computes D from the bf16 o alone (the
+ * result is then what it is without the reserve, never worse).  The explicit o_lo tensor of the
+ * _ex entry points does the same through caller memory and takes precedence.  Not written by
+ * sp_attn_fwd_multi or by the naive baseline schedule. */
+size_t sp_attn_reserve_bytes(int64_t total_tokens, int32_t n_q_heads, int32_t head_dim, sp_dtype dtype);
 
 /* Forward for one group (Section 4.3, modifications 1 and 3): writes
  * o [T, n_q_heads, head_dim] and lse [n_q_heads, T], T = prompt_len + sum(resp_lens).

@@ -21,7 +21,7 @@ SP_SCHED_SHARED, SP_SCHED_NAIVE_CAUSAL = 0, 1
 SP_BWD_STAGE_ROWSUM, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2, 4, 7
 SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 
-EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
+EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_reserve_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
            "sp_attn_bwd_batched", "sp_attn_bwd_batched_static", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
            "sp_attn_loss_workspace_bytes", "sp_attn_logprob_fwd", "sp_attn_logprob_bwd", "sp_attn_grpo_loss",
            "sp_attn_segment_table", "sp_attn_mfma_ceiling", "sp_attn_last_error", "sp_attn_version")
@@ -48,6 +48,8 @@ def load_library() -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int32)
     lib.sp_attn_workspace_bytes.restype = sz
     lib.sp_attn_workspace_bytes.argtypes = [ctypes.c_int, i64, i32, i64, i32, i32, i32, ctypes.c_int]
+    lib.sp_attn_reserve_bytes.restype = sz
+    lib.sp_attn_reserve_bytes.argtypes = [i64, i32, i32, ctypes.c_int]
     lib.sp_attn_fwd.restype = ctypes.c_int
     lib.sp_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i32, ip, i32, i32, i32, i32, f32, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_bwd.restype = ctypes.c_int
@@ -139,11 +141,27 @@ def workspace_bytes(is_bwd: bool, total_tokens: int, n_groups: int, total_respon
                                                   n_kv_heads, head_dim, dtype_code)
 
 
-def _workspace(is_bwd, q, n_groups, n_resp, n_kv_heads, workspace):
+def reserve_bytes(total_tokens: int, n_q_heads: int, head_dim: int, dtype_code: int) -> int:
+    return load_library().sp_attn_reserve_bytes(total_tokens, n_q_heads, head_dim, dtype_code)
+
+
+def _workspace(is_bwd, q, n_groups, n_resp, n_kv_heads, workspace, o=None, reserve=False):
+    """The workspace tensor of a call.  When the caller passes none: a forward allocates one that also has
+    room for the forward-to-backward reserve and hangs it on the output tensor it returns (attribute
+    ``_sp_workspace``); the backward that is given that output finds it there and passes it on, which is
+    all the library needs to use the reserve.  Plumbing only: what the reserve is and whether it is valid
+    is decided by the library."""
     T, Hq, d = q.shape
-    need = workspace_bytes(is_bwd, T, n_groups, n_resp, Hq, n_kv_heads, d, _dtype_code(q))
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        return workspace
+    if is_bwd and o is not None and getattr(o, "_sp_workspace", None) is not None:
+        return o._sp_workspace
+    need = workspace_bytes(is_bwd or reserve, T, n_groups, n_resp, Hq, n_kv_heads, d, _dtype_code(q))
+    if reserve:
+        need += reserve_bytes(T, Hq, d, _dtype_code(q))
+    workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if reserve and o is not None:
+        o._sp_workspace = workspace        # sized for the backward too
     return workspace
 
 
@@ -155,7 +173,7 @@ def sp_attn_fwd(q, k, v, prompt_len: int, resp_lens: Sequence[int], softmax_scal
     Hkv = k.shape[1]
     o = torch.empty_like(q) if o is None else o
     lse = torch.empty(Hq, T, dtype=torch.float32, device=q.device) if lse is None else lse
-    workspace = _workspace(False, q, 1, len(resp_lens), Hkv, workspace)
+    workspace = _workspace(False, q, 1, len(resp_lens), Hkv, workspace, o=o, reserve=True)
     _check(lib.sp_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), prompt_len,
                            _i32(resp_lens), len(resp_lens), Hq, Hkv, d, softmax_scale, _dtype_code(q),
                            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
@@ -171,7 +189,7 @@ def sp_attn_bwd(q, k, v, o, lse, d_o, prompt_len: int, resp_lens: Sequence[int],
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv
-    workspace = _workspace(True, q, 1, len(resp_lens), Hkv, workspace)
+    workspace = _workspace(True, q, 1, len(resp_lens), Hkv, workspace, o=o)
     _check(lib.sp_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
                            dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), prompt_len, _i32(resp_lens),
                            len(resp_lens), Hq, Hkv, d, softmax_scale, _dtype_code(q), workspace.data_ptr(),
@@ -187,7 +205,7 @@ def sp_attn_fwd_batched(q, k, v, prompt_lens: Sequence[int], Gs: Sequence[int], 
     Hkv = k.shape[1]
     o = torch.empty_like(q) if o is None else o
     lse = torch.empty(Hq, T, dtype=torch.float32, device=q.device) if lse is None else lse
-    workspace = _workspace(False, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    workspace = _workspace(False, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace, o=o, reserve=True)
     _check(lib.sp_attn_fwd_batched(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                    len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d,
                                    softmax_scale, _dtype_code(q), schedule, workspace.data_ptr(),
@@ -222,7 +240,7 @@ def sp_attn_fwd_batched_ex(q, k, v, prompt_lens: Sequence[int], Gs: Sequence[int
     Hkv = k.shape[1]
     o = torch.empty_like(q) if o is None else o
     lse = torch.empty(Hq, T, dtype=torch.float32, device=q.device) if lse is None else lse
-    workspace = _workspace(False, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    workspace = _workspace(False, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace, o=o, reserve=o_lo is None)
     _check(lib.sp_attn_fwd_batched_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                       len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d,
                                       softmax_scale, _dtype_code(q), schedule, flags,
@@ -241,7 +259,7 @@ def sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs:
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv
-    workspace = _workspace(True, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    workspace = _workspace(True, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace, o=o)
     _check(lib.sp_attn_bwd_batched_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                       d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), len(prompt_lens),
                                       _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
@@ -326,7 +344,7 @@ def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Se
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv
-    workspace = _workspace(True, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace)
+    workspace = _workspace(True, q, len(prompt_lens), len(resp_lens_flat), Hkv, workspace, o=o)
     _check(lib.sp_attn_bwd_batched(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                    d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), len(prompt_lens),
                                    _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,

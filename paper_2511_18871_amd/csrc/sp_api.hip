@@ -31,6 +31,13 @@ sp_status fail(sp_status code, const char* fmt, ...) {
 }
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Every workspace starts with a tag block of TAG_BYTES; the segment table follows it.  The tag says
+// whether the workspace holds a forward's reserve (the part of o that its rounding to bf16 dropped) and for
+// which outputs; every call rewrites or re-validates it before it writes anything else, so a reserve
+// that some other call may have overwritten is never trusted.
+constexpr size_t TAG_BYTES = 256;
+inline int* table_of(void* workspace) { return (int*)((char*)workspace + TAG_BYTES); }
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
 
 size_t table_words(int32_t n_groups, int64_t total_responses) {
@@ -137,12 +144,35 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
         return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
                     workspace_bytes, need);
 
+    // The reserve sits behind everything a backward of this problem keeps in the workspace, so the
+    // forward and its backward find it at the same offset.
+    const size_t reserve_off = align256(sp_attn_workspace_bytes(1, L.total_tokens, n_groups, L.total_responses, Hq, Hkv, d, dtype));
+    const size_t reserve_len = sp_attn_reserve_bytes(L.total_tokens, Hq, d, dtype);
+    const bool reserve_fits = reserve_len > 0 && workspace_bytes >= reserve_off + reserve_len;
+    void* const reserve = (char*)workspace + reserve_off;
+    const bool resp_only = (flags & SP_FLAG_RESPONSE_ROWS) != 0;
+    sp::ReserveTag tag{};
+    int tag_mode = sp::TAG_CLEAR;
+    if (reserve_fits && !o_lo && !(bwd == false && schedule == SP_SCHED_NAIVE_CAUSAL)) {
+        const uint64_t po = (uint64_t)(uintptr_t)(bwd ? o : o_out), pl = (uint64_t)(uintptr_t)(bwd ? (const void*)lse : (const void*)lse_out);
+        tag.w[0] = sp::TAG_MAGIC;
+        tag.w[1] = (uint32_t)po; tag.w[2] = (uint32_t)(po >> 32);
+        tag.w[3] = (uint32_t)pl; tag.w[4] = (uint32_t)(pl >> 32);
+        tag.w[5] = (uint32_t)L.total_tokens; tag.w[6] = (uint32_t)Hq; tag.w[7] = (uint32_t)d;
+        tag.w[8] = (uint32_t)reserve_off; tag.w[9] = (uint32_t)((uint64_t)reserve_off >> 32);
+        tag.w[10] = resp_only ? 1u : 0u;        // a reserve written for response rows only serves only such a backward
+        tag_mode = bwd ? sp::TAG_CHECK : sp::TAG_WRITE;
+    }
+    // gradient stages enqueued on their own run on the workspace that their ROWSUM stage prepared (and
+    // checked): the tag is left as it is
+    const bool keep_tag = bwd && !(stages & SP_BWD_STAGE_ROWSUM);
+
     hipStream_t s = (hipStream_t)stream;
     sp::Problem p{};
     p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse; p.d_o = d_o;
     p.o_out = o_out; p.lse_out = lse_out; p.dq = dq; p.dk = dk; p.dv = dv;
-    p.tab = (const int*)workspace;
-    p.Dbuf = (float*)((char*)workspace + align256(L.words.size() * 4));
+    p.tab = table_of(workspace);
+    p.Dbuf = (float*)((char*)workspace + TAG_BYTES + align256(L.words.size() * 4));
     p.dkdv_partial = (bwd && dtype == SP_BF16 && sp::dkdv_head_split(L.total_tokens, n_groups, Hq, Hkv))
                          ? (float*)((char*)p.Dbuf + align256((size_t)Hq * (size_t)L.total_tokens * 8)) : nullptr;
     p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
@@ -150,13 +180,17 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.Hq = Hq; p.Hkv = Hkv; p.head_dim = d; p.scale = scale;
     p.naive = schedule == SP_SCHED_NAIVE_CAUSAL;
     p.stages = stages;
-    p.resp_only = (flags & SP_FLAG_RESPONSE_ROWS) != 0;
-    p.o_lo_out = bwd ? nullptr : o_lo;
-    p.o_lo = bwd ? o_lo : nullptr;
+    p.resp_only = resp_only;
+    // rounding residual of o: the caller's tensor if given, else the workspace's reserve (forward: written
+    // when the workspace has room for it; backward: used if the tag check on the device finds it valid)
+    p.o_lo_out = bwd ? nullptr : (o_lo ? o_lo : (tag_mode == sp::TAG_WRITE ? reserve : nullptr));
+    p.o_lo = bwd ? (o_lo ? o_lo : (tag_mode == sp::TAG_CHECK ? reserve : nullptr)) : nullptr;
+    p.o_lo_flag = (bwd && !o_lo && tag_mode == sp::TAG_CHECK) ? (const uint32_t*)workspace + sp::TAG_FLAG_WORD : nullptr;
     p.accumulate = (flags & SP_FLAG_ACCUMULATE_DKDV) != 0;
     p.host_group_tokens = L.group_tokens.data();
 
-    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    hipError_t e = keep_tag ? hipSuccess : sp::launch_reserve_tag((uint32_t*)workspace, tag, tag_mode, s);
+    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
     if (e == hipSuccess) {
         if (dtype == SP_BF16) e = bwd ? sp::launch_bwd_bf16(p, s) : sp::launch_fwd_bf16(p, s);
         else e = bwd ? sp::launch_bwd_f32(p, s) : sp::launch_fwd_f32(p, s);
@@ -173,12 +207,17 @@ size_t sp_attn_workspace_bytes(int is_bwd, int64_t total_tokens, int32_t n_group
                                int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, sp_dtype dtype) {
     (void)head_dim;
     if (total_tokens < 1 || n_groups < 1 || total_responses < 0 || n_q_heads < 1) return 0;
-    size_t bytes = align256(table_words(n_groups, total_responses) * 4);
+    size_t bytes = TAG_BYTES + align256(table_words(n_groups, total_responses) * 4);
     if (is_bwd) bytes += align256((size_t)n_q_heads * (size_t)total_tokens * 8);   // D and scaled LSE
     if (is_bwd && dtype == SP_BF16 && n_kv_heads > 0 && n_q_heads % n_kv_heads == 0 &&
         sp::dkdv_head_split(total_tokens, n_groups, n_q_heads, n_kv_heads))       // per-q-head dK, dV partials
         bytes += align256((size_t)2 * (n_q_heads / n_kv_heads) * (size_t)total_tokens * n_kv_heads * 128 * 4);
     return bytes;
+}
+
+size_t sp_attn_reserve_bytes(int64_t total_tokens, int32_t n_q_heads, int32_t head_dim, sp_dtype dtype) {
+    if (total_tokens < 1 || n_q_heads < 1 || head_dim < 1 || dtype != SP_BF16) return 0;
+    return align256((size_t)total_tokens * (size_t)n_q_heads * (size_t)head_dim * 2);
 }
 
 sp_status sp_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int32_t prompt_len,
@@ -285,12 +324,13 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
                     workspace_bytes, need);
     hipStream_t s = (hipStream_t)stream;
     sp::Problem p{};
-    p.tab = (const int*)workspace;
+    p.tab = table_of(workspace);
     p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
     p.total_responses = L.total_responses; p.min_prompt_len = L.min_prompt_len;
     p.Hq = n_q_heads; p.Hkv = n_kv_heads; p.head_dim = head_dim; p.scale = softmax_scale;
     p.host_group_tokens = L.group_tokens.data();
-    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
+    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
     if (e == hipSuccess) {
         if (dtype == SP_BF16) {
             p.n_sets = n_sets;
@@ -329,9 +369,10 @@ sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
         return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
                     workspace_bytes, need);
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
+    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
     if (e == hipSuccess)
-        e = sp::launch_rope(x, y, (const int*)workspace, L.total_tokens, n_heads, head_dim, rope_base, inverse != 0,
+        e = sp::launch_rope(x, y, table_of(workspace), L.total_tokens, n_heads, head_dim, rope_base, inverse != 0,
                             dtype == SP_F32, s);
     if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
     return SP_OK;
@@ -339,7 +380,7 @@ sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
 
 size_t sp_attn_loss_workspace_bytes(int64_t total_tokens, int32_t n_groups, int64_t total_responses) {
     if (total_tokens < 1 || n_groups < 1 || total_responses < 0) return 0;
-    return align256(table_words(n_groups, total_responses) * 4) + align256((size_t)(total_responses + 1) * 4);
+    return TAG_BYTES + align256(table_words(n_groups, total_responses) * 4) + align256((size_t)(total_responses + 1) * 4);
 }
 
 namespace {
@@ -352,8 +393,9 @@ sp_status loss_setup(int32_t n_groups, const int32_t* prompt_lens, const int32_t
     if (!workspace || misaligned(workspace) || workspace_bytes < need)
         return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
                     workspace_bytes, need);
-    *scratch = (float*)((char*)workspace + align256(L.words.size() * 4));
-    hipError_t e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), (int*)workspace, s);
+    *scratch = (float*)((char*)workspace + TAG_BYTES + align256(L.words.size() * 4));
+    hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
+    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
     if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
     return SP_OK;
 }
@@ -371,7 +413,7 @@ sp_status sp_attn_logprob_fwd(const void* logits, const int32_t* labels, float* 
     Layout L; float* scratch = nullptr;
     sp_status st = loss_setup(n_groups, prompt_lens, Gs, resp_lens_flat, workspace, workspace_bytes, (hipStream_t)stream, L, &scratch);
     if (st != SP_OK) return st;
-    hipError_t e = sp::launch_logprob_fwd(logits, labels, logp, lse, (const int*)workspace, L.total_tokens, vocab,
+    hipError_t e = sp::launch_logprob_fwd(logits, labels, logp, lse, table_of(workspace), L.total_tokens, vocab,
                                           dtype == SP_F32, (hipStream_t)stream);
     if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
     return SP_OK;
@@ -389,7 +431,7 @@ sp_status sp_attn_logprob_bwd(const void* logits, const int32_t* labels, const f
     Layout L; float* scratch = nullptr;
     sp_status st = loss_setup(n_groups, prompt_lens, Gs, resp_lens_flat, workspace, workspace_bytes, (hipStream_t)stream, L, &scratch);
     if (st != SP_OK) return st;
-    hipError_t e = sp::launch_logprob_bwd(logits, labels, lse, g, dlogits, (const int*)workspace, L.total_tokens, vocab,
+    hipError_t e = sp::launch_logprob_bwd(logits, labels, lse, g, dlogits, table_of(workspace), L.total_tokens, vocab,
                                           dtype == SP_F32, (hipStream_t)stream);
     if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
     return SP_OK;
@@ -408,7 +450,7 @@ sp_status sp_attn_grpo_loss(const float* logp, const float* logp_old, const floa
     if (st != SP_OK) return st;
     int nonempty = 0;
     for (int64_t r = 0; r < L.total_responses; ++r) nonempty += resp_lens_flat[r] > 0;
-    hipError_t e = sp::launch_grpo(logp, logp_old, logp_ref, adv, g, scratch, loss, (const int*)workspace,
+    hipError_t e = sp::launch_grpo(logp, logp_old, logp_ref, adv, g, scratch, loss, table_of(workspace),
                                    (int)L.total_responses, nonempty, eps_low, eps_high, beta, (hipStream_t)stream);
     if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
     return SP_OK;

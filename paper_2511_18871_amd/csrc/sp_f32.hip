@@ -25,6 +25,20 @@ __global__ void upload_table_kernel(TabChunk chunk, int* __restrict__ dst, int o
     for (int i = threadIdx.x; i < count; i += blockDim.x) dst[offset + i] = chunk.w[i];
 }
 
+// Tag block maintenance, one wave.  See sp_launch.hpp for the modes.  A reserve written for all rows
+// (word 10 = 0) also serves a backward over response rows only (want word 10 = 1), not the reverse.
+__global__ __launch_bounds__(64) void reserve_tag_kernel(uint32_t* __restrict__ blk, ReserveTag want, int mode) {
+    const int i = threadIdx.x;
+    if (mode == TAG_CLEAR) { blk[i] = 0u; return; }
+    if (mode == TAG_WRITE) { blk[i] = i < TAG_WORDS ? want.w[i] : 0u; return; }
+    const uint32_t have = blk[i];
+    bool same = i >= TAG_WORDS || have == want.w[i];
+    if (i == 10) same = have == want.w[10] || have == 0u;
+    const bool ok = __builtin_amdgcn_ballot_w64(!same) == 0;
+    if (i < TAG_WORDS && !ok) blk[i] = 0u;
+    if (i == TAG_FLAG_WORD) blk[i] = ok ? 1u : 0u;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, const T* __restrict__ o,
                                                      const float* __restrict__ lse, float* __restrict__ D,
@@ -76,9 +90,12 @@ template <bool HAS_LO>
 __global__ __launch_bounds__(256) void rowsum_bf16_kernel(const __bf16* __restrict__ d_o, const __bf16* __restrict__ o,
                                                           const float* __restrict__ lse, float* __restrict__ D,
                                                           int64_t T_total, int Hq, const int* __restrict__ tab,
-                                                          int resp_only, const __bf16* __restrict__ o_lo) {
+                                                          int resp_only, const __bf16* __restrict__ o_lo,
+                                                          const uint32_t* __restrict__ lo_flag) {
     extern __shared__ float rs_sum[];                  // [Hq][RS_TOK]
     __shared__ int rs_skip[RS_TOK];
+    // the residual is the workspace's reserve: usable only if the tag check of this call said so
+    const bool use_lo = HAS_LO && (lo_flag == nullptr || __builtin_amdgcn_readfirstlane((int)*lo_flag) != 0);
     const int64_t tok0 = (int64_t)blockIdx.x * RS_TOK;
     const int ntok = (int)(T_total - tok0 < RS_TOK ? T_total - tok0 : RS_TOK);
     const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4;
@@ -98,7 +115,7 @@ __global__ __launch_bounds__(256) void rowsum_bf16_kernel(const __bf16* __restri
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(d_o + off);
         const bf16x8 b = *reinterpret_cast<const bf16x8*>(o + off);
         float acc = 0.f;
-        if (HAS_LO) {        // o was stored with its rounding residual: D from the unrounded value
+        if (HAS_LO && use_lo) {        // o was stored with its rounding residual: D from the unrounded value
             const bf16x8 c = *reinterpret_cast<const bf16x8*>(o_lo + off);
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)a[e], (float)b[e] + (float)c[e], acc);
@@ -386,6 +403,11 @@ inline int blocks_for_waves(int64_t waves) { return (int)((waves + 3) / 4); }
 
 }  // namespace
 
+hipError_t launch_reserve_tag(uint32_t* tag_block, const ReserveTag& tag, int mode, hipStream_t s) {
+    hipLaunchKernelGGL(reserve_tag_kernel, dim3(1), dim3(64), 0, s, tag_block, tag, mode);
+    return hipGetLastError();
+}
+
 hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s) {
     for (int off = 0; off < n_words; off += TAB_CHUNK_WORDS) {
         TabChunk c;
@@ -409,10 +431,11 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
         const size_t lds = (size_t)p.Hq * RS_TOK * sizeof(float);
         if (p.o_lo)
             hipLaunchKernelGGL(rowsum_bf16_kernel<true>, g, dim3(256), lds, s, (const __bf16*)p.d_o, (const __bf16*)p.o,
-                               p.lse, p.Dbuf, p.total_tokens, p.Hq, p.tab, p.resp_only, (const __bf16*)p.o_lo);
+                               p.lse, p.Dbuf, p.total_tokens, p.Hq, p.tab, p.resp_only, (const __bf16*)p.o_lo, p.o_lo_flag);
         else
             hipLaunchKernelGGL(rowsum_bf16_kernel<false>, g, dim3(256), lds, s, (const __bf16*)p.d_o, (const __bf16*)p.o,
-                               p.lse, p.Dbuf, p.total_tokens, p.Hq, p.tab, p.resp_only, (const __bf16*)nullptr);
+                               p.lse, p.Dbuf, p.total_tokens, p.Hq, p.tab, p.resp_only, (const __bf16*)nullptr,
+                               (const uint32_t*)nullptr);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         // exact D for the rows with at most RS_SHORT keys.  Prompts: one item per group (none in
@@ -430,7 +453,8 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
     }
     else
         hipLaunchKernelGGL(rowsum_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)p.d_o,
-                           (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only, (const __bf16*)p.o_lo);
+                           (const __bf16*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only,
+                           (const __bf16*)(p.o_lo_flag ? nullptr : p.o_lo));      // this fallback does not consult the reserve
     return hipGetLastError();
 }
 

@@ -8,6 +8,18 @@ namespace sp {
 constexpr unsigned STAGE_ROWSUM = 1u, STAGE_DKDV = 2u, STAGE_DQ = 4u;
 constexpr int MAX_SETS = 4;      // tensor sets that one forward launch can serve
 
+// Tag block at the head of every workspace (64 words).  Words 0..TAG_WORDS-1 describe the reserve a
+// forward left in this workspace (magic, o and lse pointers, token count, heads, head_dim, byte offset of
+// the reserve, response-rows-only flag); word TAG_FLAG_WORD is the verdict of the latest check.
+constexpr int TAG_WORDS = 12;
+constexpr int TAG_FLAG_WORD = 15;
+constexpr uint32_t TAG_MAGIC = 0x53504152u;
+struct ReserveTag { uint32_t w[TAG_WORDS]; };
+// TAG_CLEAR: the workspace holds no reserve from here on.  TAG_WRITE: a forward is about to write the
+// reserve that `tag` describes.  TAG_CHECK: a backward asks whether the workspace holds exactly the
+// reserve `tag` describes; if not, the tag is cleared (the call is about to write into the workspace).
+constexpr int TAG_CLEAR = 0, TAG_WRITE = 1, TAG_CHECK = 2;
+
 struct Problem {
     const void* q; const void* k; const void* v;
     const void* o; const float* lse; const void* d_o;     // backward inputs (o also fwd output)
@@ -32,6 +44,7 @@ struct Problem {
     int resp_only;                                        // only response rows are computed / contribute
     void* o_lo_out;                                       // forward (bf16): optional rounding residual of o
     const void* o_lo;                                     // backward (bf16): optional residual for D
+    const uint32_t* o_lo_flag;                            // device word: o_lo may be used only if it is non-zero (NULL: always)
     int accumulate;                                       // backward: dk, dv += instead of =
     float* dkdv_partial;                                  // bf16 backward on small problems: fp32 per-q-head partials
     // host copies of the per-group token counts, for grid sizing
@@ -52,6 +65,7 @@ hipError_t launch_logprob_bwd(const void* z, const int* y, const float* lse, con
 hipError_t launch_grpo(const float* logp, const float* old, const float* ref, const float* adv, float* g,
                        float* J, float* loss, const int* tab, int n_resp, int n_nonempty, float eps_low,
                        float eps_high, float beta, hipStream_t s);
+hipError_t launch_reserve_tag(uint32_t* tag_block, const ReserveTag& tag, int mode, hipStream_t s);
 hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s);
 
 inline int count_tiles(const Problem& p, int bm) {

@@ -47,19 +47,57 @@ def run_gpu(w, t, backward):
     return [x.cpu() for x in out]
 
 
-def check_sampled(w, t, got, backward, groups, n_rows, heads, kv_check=None):
+def head_per_kv_head(w):
+    """One q head of every kv head, at a different position inside each GQA block."""
+    rep = w.n_q_heads // w.n_kv_heads
+    return [g * rep + g % rep for g in range(w.n_kv_heads)]
+
+
+def check_sampled(w, t, got, backward, groups, n_rows, heads, kv_check=None, full_head=None):
+    """O / LSE / dQ of `n_rows` sampled rows (plus the edge rows) for `heads`, per group; the rows that see
+    at least 4096 keys are also gated on their own, so that the few short rows of a sample (outputs of
+    order one) cannot carry the long ones (outputs of order 1e-2) through the relative gate.  dK / dV of
+    one whole kv head (`kv_check` = (group, kv head)); every row of one q head (`full_head` = (group, head))."""
     rng = np.random.default_rng(123)
     for gi, (sl, g) in enumerate(group_slices(w)):
         if gi not in groups:
             continue
         rows = sample_rows(g, rng, n_rows)
+        seg_start = np.zeros(g.total, dtype=np.int64)
+        off = g.prompt_len
+        for li in g.resp_lens:
+            seg_start[off:off + li] = off
+            off += li
+        n_keys = np.array([r + 1 if r < g.prompt_len else g.prompt_len + r - seg_start[r] + 1 for r in rows])
+        long_rows = np.nonzero(n_keys >= 4096)[0]
         qg, kg, vg = t.q[sl], t.k[sl], t.v[sl]
         ro, rlse = orc.sp_attn_fwd(qg, kg, vg, g.prompt_len, g.resp_lens, w.softmax_scale, rows=rows, heads=heads)
-        print(gate(f"O[g{gi}]", to64(got[0][sl])[rows][:, heads], ro, w.dtype))
+        go = to64(got[0][sl])[rows][:, heads]
+        print(gate(f"O[g{gi}, {len(rows)} rows x {len(heads)} heads]", go, ro, w.dtype))
+        if len(long_rows):
+            print(gate(f"O[g{gi}, {len(long_rows)} rows with >= 4096 keys]", go[long_rows], ro[long_rows], w.dtype))
         gate_lse(to64(got[1][:, sl])[heads][:, rows], rlse, w.dtype)
         if backward:
             rdq = orc.sp_attn_bwd_rows(qg, kg, vg, t.d_o[sl], g.prompt_len, g.resp_lens, w.softmax_scale, rows, heads)
-            print(gate(f"dQ[g{gi}]", to64(got[2][sl])[rows][:, heads], rdq, w.dtype))
+            gdq = to64(got[2][sl])[rows][:, heads]
+            print(gate(f"dQ[g{gi}, {len(rows)} rows x {len(heads)} heads]", gdq, rdq, w.dtype))
+            if len(long_rows):
+                print(gate(f"dQ[g{gi}, {len(long_rows)} rows with >= 4096 keys]", gdq[long_rows], rdq[long_rows], w.dtype))
+    if full_head is not None:
+        gi, h = full_head
+        sl, g = list(group_slices(w))[gi]
+        kvh = h // (w.n_q_heads // w.n_kv_heads)
+        # the head's own slices ([T, 1, d] each, so q head 0 reads kv head 0): nothing else is converted to fp64
+        qh, kh, vh = t.q[sl][:, [h]], t.k[sl][:, [kvh]], t.v[sl][:, [kvh]]
+        ro, rlse = orc.sp_attn_fwd(qh, kh, vh, g.prompt_len, g.resp_lens, w.softmax_scale, row_block=2048)
+        print(gate(f"O[g{gi}, every row of head {h}]", to64(got[0][sl])[:, [h]], ro, w.dtype))
+        gate_lse(to64(got[1][:, sl])[[h]], rlse, w.dtype)
+        if backward:
+            gh = t.d_o[sl][:, [h]]
+            rdq = np.concatenate([orc.sp_attn_bwd_rows(qh, kh, vh, gh, g.prompt_len, g.resp_lens, w.softmax_scale,
+                                                       list(range(a, min(a + 4096, g.total))), [0])
+                                  for a in range(0, g.total, 4096)])
+            print(gate(f"dQ[g{gi}, every row of head {h}]", to64(got[2][sl])[:, [h]], rdq, w.dtype))
     if backward and kv_check is not None:
         gi, kvh = kv_check
         sl, g = list(group_slices(w))[gi]
@@ -73,7 +111,7 @@ def test_config3_ragged_multi_group():
     w = W.config(3)
     t = W.make_tensors(w)
     got = run_gpu(w, t, True)
-    check_sampled(w, t, got, True, groups=(0, 3), n_rows=24, heads=[0, 13, 31], kv_check=(1, 5))
+    check_sampled(w, t, got, True, groups=(0, 3), n_rows=512, heads=head_per_kv_head(w), kv_check=(1, 5), full_head=(2, 13))
 
 
 def test_config4_tri_model_forward_batched_and_per_set():
@@ -82,7 +120,7 @@ def test_config4_tri_model_forward_batched_and_per_set():
     sets = [W.make_tensors(w, s) for s in range(3)]
     per_set = [run_gpu(w, t, False) for t in sets]
     for s in (0, 2):
-        check_sampled(w, sets[s], per_set[s], False, groups=(0, 7), n_rows=16, heads=[0, 27])
+        check_sampled(w, sets[s], per_set[s], False, groups=(0, 7), n_rows=256, heads=head_per_kv_head(w))
     w3 = W.Workload("c4_all_sets", w.groups * 3, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.seed,
                     backward=False)
     cat = W.Tensors(torch.cat([t.q for t in sets]), torch.cat([t.k for t in sets]),
@@ -99,7 +137,7 @@ def test_config5_extreme_sharing_large_logits():
     t = W.make_tensors(w)
     assert len(t.stressed_rows) > 100          # about 1 % of the K rows carry the x8 scale
     got = run_gpu(w, t, True)
-    check_sampled(w, t, got, True, groups=(0,), n_rows=40, heads=[0, 17, 39], kv_check=(0, 3))
+    check_sampled(w, t, got, True, groups=(0,), n_rows=512, heads=head_per_kv_head(w), kv_check=(0, 3), full_head=(0, 17))
 
 
 def test_config5_residual_of_o_tightens_dq():

@@ -102,9 +102,7 @@ def test_staged_backward_equals_single_call():
     pl, Gs, rl = w.prompt_lens(), w.Gs(), w.resp_lens_flat()
     o, lse = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, w.softmax_scale)
     dq, dk, dv = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, w.softmax_scale)
-    T, Hq, d = q.shape
-    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, k.shape[1], d, B.SP_BF16), dtype=torch.uint8,
-                     device="cuda")
+    ws = o._sp_workspace            # the forward's workspace (the single call above used it too)
     dq2, dk2, dv2 = torch.empty_like(dq), torch.empty_like(dk), torch.empty_like(dv)
     B.sp_attn_bwd_batched_stages(q, k, v, o, lse, d_o, pl, Gs, rl, w.softmax_scale, B.SP_BWD_STAGE_ROWSUM, ws)
     B.sp_attn_bwd_batched_stages(q, k, v, None, lse, d_o, pl, Gs, rl, w.softmax_scale, B.SP_BWD_STAGE_DQ, ws, dq=dq2)
@@ -184,11 +182,11 @@ def test_forward_and_backward_replay_from_a_captured_graph():
 def test_large_logits_keep_the_softmax_in_range(gain):
     """Scores with a standard deviation of tens to hundreds: rows are near one-hot, the row maximum
     jumps by hundreds of units between tiles (every jump takes the forward's re-reference path) and
-    exp underflows everywhere else.  Outputs must stay finite and at the usual tolerances.  dQ is
-    the exception on the plain entry points: in a one-hot row dS = P (dP - D) cancels to almost
-    nothing and D = rowsum(dO * o) carries the bf16 rounding of o, so dQ is held to the gates only
-    when the forward hands the rounding residual of o to the backward (o_lo), and to twice the
-    relative-RMS gate otherwise."""
+    exp underflows everywhere else.  Outputs must stay finite and at the usual tolerances on the
+    default path (forward and backward share a workspace with room for the reserve) and with the
+    explicit rounding residual o_lo.  Without either, in a one-hot row dS = P (dP - D) cancels to
+    almost nothing and D = rowsum(dO * o) carries the bf16 rounding of o: that fallback is only
+    required to stay finite and within twice the relative-RMS gate."""
     w = W.Workload("hot", [W.Group(300, [130, 0, 64, 77])], 4, 2, 128, torch.bfloat16, 99)
     t = W.make_tensors(w)
     t.q.mul_(gain)
@@ -197,19 +195,27 @@ def test_large_logits_keep_the_softmax_in_range(gain):
     q, k, v, d_o = (x.cuda() for x in (t.q, t.k, t.v, t.d_o))
     o_lo = torch.empty_like(q)
     o, lse = B.sp_attn_fwd_batched_ex(q, k, v, pl, Gs, rl, sc, 0, o_lo=o_lo)
-    dq0, dk0, dv0 = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc)
+    T, Hq, d = q.shape
+    small = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, k.shape[1], d, B.SP_BF16), dtype=torch.uint8,
+                        device="cuda")                 # no room for a reserve: the fallback
+    dq0, dk0, dv0 = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc, workspace=small)
     dq, dk, dv = B.sp_attn_bwd_batched_ex(q, k, v, o, lse, d_o, pl, Gs, rl, sc, 0, o_lo=o_lo)
+    o1, lse1 = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, sc)          # default path: reserve in the workspace
+    dq1, dk1, dv1 = B.sp_attn_bwd_batched(q, k, v, o1, lse1, d_o, pl, Gs, rl, sc)
     torch.cuda.synchronize()
+    assert torch.equal(o1, o) and torch.equal(lse1, lse)
     rdq, rdk, rdv, ro, rlse = oracle_bwd(w, t)
     assert float(np.abs(rlse).max()) > 4.0 * gain * gain    # the scores really are that large
     gate("O", to64(o), ro, w.dtype)
     err = np.abs(to64(lse) - rlse)
     assert float((err - (1e-4 + 3e-7 * np.abs(rlse))).max()) <= 0.0      # fp32 LSE of magnitude 1e2..1e4
-    gate("dQ[o_lo]", to64(dq), rdq, w.dtype)
-    gate("dK[o_lo]", to64(dk), rdk, w.dtype)
-    gate("dV[o_lo]", to64(dv), rdv, w.dtype)
-    gate("dK", to64(dk0), rdk, w.dtype)
-    gate("dV", to64(dv0), rdv, w.dtype)
+    for tag, (a, b, c) in (("o_lo", (dq, dk, dv)), ("default", (dq1, dk1, dv1))):
+        gate(f"dQ[{tag}]", to64(a), rdq, w.dtype)
+        gate(f"dK[{tag}]", to64(b), rdk, w.dtype)
+        gate(f"dV[{tag}]", to64(c), rdv, w.dtype)
+    assert torch.equal(dq1, dq) and torch.equal(dk1, dk) and torch.equal(dv1, dv)   # the reserve IS that residual
+    gate("dK[fallback]", to64(dk0), rdk, w.dtype)
+    gate("dV[fallback]", to64(dv0), rdv, w.dtype)
     e0 = to64(dq0) - rdq
     assert np.all(np.isfinite(e0))
     assert float(np.sqrt(np.mean(e0 ** 2)) / np.sqrt(np.mean(rdq ** 2))) <= 1e-2

@@ -17,7 +17,11 @@ def _case(w):
     pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
     q, k, v, d_o = (x.cuda() for x in (t.q, t.k, t.v, t.d_o))
     o, lse = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, sc)
-    want = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc)
+    T, Hq, d = q.shape
+    code = B.SP_BF16 if q.dtype == torch.bfloat16 else B.SP_F32
+    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, k.shape[1], d, code), dtype=torch.uint8, device="cuda")
+    # the workspace entry point on a workspace without a forward's reserve, as the static scratch is
+    want = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc, workspace=ws)
     torch.cuda.synchronize()
     return t, (q, k, v, o, lse, d_o), (pl, Gs, rl, sc), want
 
