@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsp_attn.so")
-SOURCES = ["sp_api.hip", "sp_f32.hip", "sp_fwd.hip", "sp_bwd.hip", "sp_rope.hip", "sp_loss.hip", "sp_probe.hip"]
+SOURCES = ["sp_api.hip", "sp_f32.hip", "sp_fwd.hip", "sp_bwd.hip", "sp_rope.hip", "sp_loss.hip", "sp_probe.hip", "sp_edge.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function", "-fno-honor-nans",
          # keep the compiler from forming packed-fp32 VALU ops

@@ -16,6 +16,7 @@
 // neither pass exchanges dS between lanes or accumulates through memory.
 #include "sp_common.hpp"
 #include "sp_launch.hpp"
+#include <type_traits>
 
 namespace sp {
 namespace {
@@ -304,7 +305,9 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     dsum = pair_sum(dsum);
     const bool store = valid && !(a.resp_only && t < Lp);
     if (store && hh == 0) a.D[(int64_t)head * T_total + gd.tok_base + t] = dsum;
-    if (store) {
+    // rows that see at most EDGE_LEN keys are written by the edge kernel (fp32 dS): not stored here
+    const bool short_row = (t < Lp ? 0 : Lp) + t - st + 1 <= EDGE_LEN;
+    if (store && !short_row) {
         __bf16* op = a.dq + ((int64_t)(gd.tok_base + t) * a.Hq + head) * 128 + 4 * hh;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -327,25 +330,14 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
 // in LDS for the whole kernel (B operands are re-read per step, which keeps a wave under 256
 // registers); Q/dO tiles stream through a double buffer.  The two row halves' partial dK/dV
 // are added through LDS at the end, in a fixed order.
-__global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
+__shared__ __attribute__((aligned(1024))) char dkdv_ldsKV[2][128 * 256];       // [K | V] of the 128 keys
+__shared__ __attribute__((aligned(1024))) char dkdv_lds[2][2 * TILE_BYTES];    // [buffer][Q | dO]
+__shared__ __attribute__((aligned(256))) float dkdv_ldsLD[2][2][64];           // [buffer][L2 | D][row]
+
+__device__ __forceinline__ void dkdv_body(const BwdArgs& a, const int g, const int ti, const int kvh, const int hr_only) {
     constexpr int BNK = 128, BQ = 64;
     constexpr int RD = 3;      // LDS operand ring depth (prefetch distance RD - 1 MFMAs)
-    __shared__ __attribute__((aligned(1024))) char ldsKV[2][BNK * 256];      // [K | V] of the 128 keys
-    __shared__ __attribute__((aligned(1024))) char lds[2][2 * TILE_BYTES];   // [buffer][Q | dO]
-    __shared__ __attribute__((aligned(256))) float ldsLD[2][2][BQ];          // [buffer][L2 | D][row]
-
-    int tile, kvh, hr_only = 0;
-    if (a.head_split) {
-        int head;
-        if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
-        kvh = head / (a.Hq / a.Hkv);
-        hr_only = head % (a.Hq / a.Hkv);
-    } else if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
-    // key tiles in ascending order: the first prompt tile is seen by every row (most work)
-    int g, ti;
-    find_tile<BNK>(a.tab, a.n_groups, tile, g, ti);
     const int s0 = ti * BNK;
-    if (g < 0) return;
     const GroupDesc gd = load_group(a.tab, g);
     const int Lp = gd.Lp, Tg = gd.Tg;
     const int64_t T_total = a.tab[1];
@@ -379,10 +371,8 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     const int row_lo = a.resp_only ? Lp : 0;
     const int s_lo = max(s, row_lo);                   // first row that contributes to this lane's key
     const int qt0 = max(s0, row_lo) / BQ, qt1 = (row_end + BQ - 1) / BQ;
-    const int nqt = max(qt1 - qt0, 0);
     const int rep_all = a.Hq / a.Hkv;
     const int rep = a.head_split ? 1 : rep_all;        // q heads this workgroup walks
-    const int total = nqt * rep;
     const int64_t q_stride = (int64_t)a.Hq * 128;
     const int64_t kv_stride = (int64_t)a.Hkv * 128;
 
@@ -398,7 +388,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
             const int gran = (l & 15) ^ swz(row);
             const int sk = min(s0 + row, Tg - 1);
             const __bf16* src = (ci < 32 ? kb_ : vb_) + (int64_t)sk * kv_stride + gran * 8;
-            async_copy16(src, &ldsKV[ci >> 5][(ci & 31) * 1024]);
+            async_copy16(src, &dkdv_ldsKV[ci >> 5][(ci & 31) * 1024]);
         }
     }
     // Row tiles are walked from the LAST one down to the workgroup's own keys: workgroups that
@@ -429,7 +419,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
     const int head0 = kvh * rep_all + hr_only;          // first q head this workgroup walks
     const uint64_t qbase_s = sgpr64(a.q + ((int64_t)gd.tok_base * a.Hq + head0) * 128);
     const uint64_t gbase_s = sgpr64(a.d_o + ((int64_t)gd.tok_base * a.Hq + head0) * 128);
-    const unsigned m0buf[2] = {lds_u32(lds[0]) + 2048u * w, lds_u32(lds[1]) + 2048u * w};
+    const unsigned m0buf[2] = {lds_u32(dkdv_lds[0]) + 2048u * w, lds_u32(dkdv_lds[1]) + 2048u * w};
     const unsigned tile_bytes = BQ * qstride_b;
     auto issue_tile = [&](int qt, int hr, int buf) {
         const uint64_t off = (uint64_t)(unsigned)qt * tile_bytes + (unsigned)hr * 256u;
@@ -453,7 +443,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
             const int head = head0 + hr;
             const int t = min(qt * BQ + l, Tg - 1);
             const float* src = (w == 0 ? a.L2 : a.D) + (int64_t)head * T_total + gd.tok_base + t;
-            async_copy4(src, reinterpret_cast<char*>(&ldsLD[buf][w][0]));
+            async_copy4(src, reinterpret_cast<char*>(&dkdv_ldsLD[buf][w][0]));
         }
     };
 
@@ -463,39 +453,51 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
     const float cs = a.c;
-    const char* ldsK = ldsKV[0];
-    const char* ldsV = ldsKV[1];
+    const char* ldsK = dkdv_ldsKV[0];
+    const char* ldsV = dkdv_ldsKV[1];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    auto pack2 = [&](float x, float y) -> unsigned {
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        bf16x2 v = {(__bf16)x, (__bf16)y};
-        return __builtin_bit_cast(unsigned, v);
-    };
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
     // Within a step the vector work is folded under the MFMAs: the exponentials of the first 8
     // rows run under the dP MFMAs (S is complete by then), those of the last 8 rows under the
     // first half of the dV/dK MFMAs (which only need the first 8 rows of P and dS).  Masking is
     // applied to S beforehand (score -inf gives P = 0 and dS = 0).
-    int qt = qt1 - 1, hr = 0;                 // step 0
+    // Rows that see only a few keys carry weights P of order one, and a key's dK / dV can be made up almost
+    // entirely of a handful of such terms, whose bf16 roundings of P and dS then do not average out.  The
+    // steps that hold such rows (the first EDGE_LEN rows of a prompt; under a shorter prompt, conservatively,
+    // every step with response rows) are therefore swept a second time after the main sweep, with P and dS
+    // replaced by what their rounding dropped, P - bf16(P) and dS - bf16(dS) (rounded to bf16 in turn): the
+    // two sweeps together carry P and dS into dV and dK to about 2^-17.  The second sweep is the same code
+    // with another packing function, outside the main loop, so it costs that loop neither registers nor time.
+    auto sweep = [&](auto lo_tag, const int q_hi, const int q_lo) {      // row tiles q_hi - 1 down to q_lo
+    constexpr bool LO = decltype(lo_tag)::value;
+    auto pack2 = [&](float x, float y) -> unsigned {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 v = {(__bf16)x, (__bf16)y};
+        if (LO) v = bf16x2{(__bf16)(x - (float)v[0]), (__bf16)(y - (float)v[1])};
+        return __builtin_bit_cast(unsigned, v);
+    };
+    const int n_steps = max(q_hi - q_lo, 0) * rep;
+    int qt = q_hi - 1, hr = 0;                // step 0
     int qt_n = qt, hr_n = 1;                  // step 1
     if (hr_n == rep) { hr_n = 0; --qt_n; }
-    if (total > 0) issue_tile(qt, hr, 0);
-    for (int it = 0; it < total; ++it) {
+    if (n_steps > 0) issue_tile(qt, hr, 0);
+    for (int it = 0; it < n_steps; ++it) {
         const int buf = it & 1;
         wait_vm0();
         __syncthreads();
-        if (it + 1 < total) issue_tile(qt_n, hr_n, buf ^ 1);
-        const char* ldsQ = lds[buf];
-        const char* ldsG = lds[buf] + TILE_BYTES;
-        const float* ldsL = ldsLD[buf][0];
-        const float* ldsD = ldsLD[buf][1];
+        if (it + 1 < n_steps) issue_tile(qt_n, hr_n, buf ^ 1);
+        const char* ldsQ = dkdv_lds[buf];
+        const char* ldsG = dkdv_lds[buf] + TILE_BYTES;
+        const float* ldsL = dkdv_ldsLD[buf][0];
+        const float* ldsD = dkdv_ldsLD[buf][1];
         const int r0 = qt * BQ + 32 * qh;              // this wave's 32 rows
         qt = qt_n; hr = hr_n;
         if (++hr_n == rep) { hr_n = 0; --qt_n; }
         // no row of this wave's half sees any key of this wave
         const bool skip = !wave_valid || r0 + 31 < max(ws0, row_lo) || r0 >= e_max;
         if (skip) continue;
+        if (LO && !(r0 < min(Lp, EDGE_LEN) || (Lp < EDGE_LEN && r0 + 31 >= Lp))) continue;   // no short row here
 
         f32x16 sacc, pacc;
         {   // S = Q K^T
@@ -624,10 +626,19 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
             }
         }
     }
+    };
+    sweep(std::false_type{}, qt1, qt0);
+    {   // the steps that can hold short rows: row tile 0 under a prompt of at least EDGE_LEN tokens, else all
+        const int f_hi = Lp >= EDGE_LEN ? min(qt1, 1) : qt1;
+        if (f_hi > qt0) {
+            __syncthreads();                       // every wave has left the main sweep's last buffer
+            sweep(std::true_type{}, f_hi, qt0);
+        }
+    }
 
     // add the two row halves: waves 4..7 park their partial sums in LDS (the Q/dO buffers,
     // 16 KB per wave), waves 0..3 add them and write the result.  dK first, then dV.
-    float* xch = reinterpret_cast<float*>(&lds[0][0]) + (size_t)kb * 4096 + l * 4;
+    float* xch = reinterpret_cast<float*>(&dkdv_lds[0][0]) + (size_t)kb * 4096 + l * 4;
     const int64_t orow = ((int64_t)(gd.tok_base + (valid ? s : 0)) * a.Hkv + kvh) * 128 + 4 * hh;
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
@@ -667,6 +678,21 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
                 }
         }
     }
+}
+
+__global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
+    int tile, kvh, hr_only = 0;
+    if (a.head_split) {
+        int head;
+        if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
+        kvh = head / (a.Hq / a.Hkv);
+        hr_only = head % (a.Hq / a.Hkv);
+    } else if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
+    // key tiles in ascending order: the first prompt tile is seen by every row (most work)
+    int g, ti;
+    find_tile<128>(a.tab, a.n_groups, tile, g, ti);
+    if (g < 0) return;
+    dkdv_body(a, g, ti, kvh, hr_only);
 }
 
 // Second stage of the head-split dkdv pass: dk = scale * sum_hr partial[0][hr], dv = sum_hr
@@ -717,6 +743,8 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
         const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
         hipLaunchKernelGGL(bwd_dq_kernel<NWQ>, dim3(grid), dim3(NWQ * 64), 0, s, a);
         e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        e = launch_short_rows(p, true, s);
         if (e != hipSuccess) return e;
     }
     if (p.stages & STAGE_DKDV) {

@@ -150,87 +150,6 @@ __global__ __launch_bounds__(256) void rowsum_bf16_kernel(const __bf16* __restri
     }
 }
 
-// D for the rows that see at most RS_SHORT keys, from its definition D = sum_s P_s dP_s in fp32
-// (P_s = exp(scale q.k_s - LSE), dP_s = dO.v_s) instead of rowsum(dO * O) with the bf16-rounded O.
-// The rounding of O puts an error of about 2^-9 |dO| |O| sqrt(d) on D whatever the row; it reaches
-// dQ as -scale * dD * sum_s P_s K_s, which averages out over a long row and does not over a short
-// one: the first rows of a group (and, under a short prompt, of each response) are where dQ's
-// largest errors sat.  Work item = (segment, q head), a segment being a group's prompt or one of
-// its responses (two launches: prompts, and responses only when some prompt is that short).  The
-// rows of an item and the keys they see (the prompt's, then the segment's own) number at most
-// RS_SHORT each, so S^T and dP^T are two 64 x 64 x 128 products: wave rb takes rows 32 rb .. + 31
-// against both 32-key blocks, operands read straight from global memory in the MFMA layout (lane
-// (c, hh): row or key c, elements 16 ks + 8 hh .. + 7), no LDS.  Runs after the rowsum kernel and
-// overwrites its D entries for these rows.
-constexpr int RS_SHORT = 64;
-__global__ __launch_bounds__(128) void rowsum_short_rows_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                                                               const __bf16* __restrict__ v, const __bf16* __restrict__ d_o,
-                                                               const float* __restrict__ lse, float* __restrict__ D,
-                                                               int64_t T_total, int n_groups, int Hq, int Hkv, float scale,
-                                                               const int* __restrict__ tab, int response_items) {
-    const int item = blockIdx.x, h = blockIdx.y;
-    int g = item, j = 0;                             // prompt items: one per group, found directly
-    if (response_items) {
-        // response items enumerate the table's response-offset words (a group's G + 1 words: its
-        // prompt's, skipped here, then one per response); the group is the one whose words hold it
-        const int word = TAB_HEADER + TAB_GROUP_WORDS * n_groups + item;
-        int lo = 0, hi = n_groups;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (tab[TAB_HEADER + TAB_GROUP_WORDS * mid + 3] <= word) lo = mid; else hi = mid;
-        }
-        g = lo;
-        j = word - tab[TAB_HEADER + TAB_GROUP_WORDS * g + 3];
-        if (j == 0) return;
-    }
-    const GroupDesc gd = load_group(tab, g);
-    if (j > gd.G) return;
-    const int seg0 = j == 0 ? 0 : gd.roff[j - 1], seg1 = j == 0 ? gd.Lp : gd.roff[j];
-    const int base_keys = j == 0 ? 0 : gd.Lp;        // prompt keys that every row of this segment sees
-    const int n_rows = min(seg1 - seg0, RS_SHORT - base_keys);           // rows with at most RS_SHORT keys
-    const int rb = threadIdx.x >> 6, l = threadIdx.x & 63, c = l & 31, hh = l >> 5;
-    if (32 * rb >= n_rows) return;
-    const int n_keys = base_keys + n_rows;           // keys seen by the last of these rows
-    const int kvh = h / (Hq / Hkv);
-    // key number x (0 .. n_keys - 1) -> group-local token: the prompt's keys, then the segment's own
-    auto key_tok = [&](int x) { x = min(x, n_keys - 1); return x < base_keys ? x : seg0 + (x - base_keys); };
-    const int r = 32 * rb + c;                       // this lane's row within the segment
-    const int64_t tok = gd.tok_base + seg0 + min(r, n_rows - 1);
-    const __bf16* qr = q + (tok * Hq + h) * 128 + 8 * hh;
-    const __bf16* gr = d_o + (tok * Hq + h) * 128 + 8 * hh;
-    bf16x8 qf[8], gf[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        qf[ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
-        gf[ks] = *reinterpret_cast<const bf16x8*>(gr + 16 * ks);
-    }
-    const float L = lse[(int64_t)h * T_total + tok];
-    const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    float acc = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-        if (32 * kb >= n_keys) break;
-        const int64_t ktok = gd.tok_base + key_tok(32 * kb + c);
-        const __bf16* kr = k + (ktok * Hkv + kvh) * 128 + 8 * hh;
-        const __bf16* vr = v + (ktok * Hkv + kvh) * 128 + 8 * hh;
-        f32x16 S = zero16, P = zero16;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            S = mfma32(*reinterpret_cast<const bf16x8*>(kr + 16 * ks), qf[ks], S);
-            P = mfma32(*reinterpret_cast<const bf16x8*>(vr + 16 * ks), gf[ks], P);
-        }
-        // element e of the result: key 32 kb + 8 (e / 4) + 4 hh + e % 4 against this lane's row
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int x = 32 * kb + 8 * (e >> 2) + 4 * hh + (e & 3);
-            const bool ok = r < n_rows && x <= base_keys + r;
-            acc += ok ? __expf(S[e] * scale - L) * P[e] : 0.f;
-        }
-    }
-    acc = pair_sum(acc);
-    if (r < n_rows && hh == 0) D[(int64_t)h * T_total + tok] = acc;
-}
-
 template <int DH>
 __device__ __forceinline__ float dot_row(const float* __restrict__ x, const float* __restrict__ y) {
     float acc = 0.f;
@@ -438,18 +357,9 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
                                (const uint32_t*)nullptr);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        // exact D for the rows with at most RS_SHORT keys.  Prompts: one item per group (none in
-        // response-rows mode, where prompt rows take no part)
-        if (!p.resp_only)
-            hipLaunchKernelGGL(rowsum_short_rows_kernel, dim3((unsigned)p.n_groups, (unsigned)p.Hq), dim3(128), 0, s,
-                               (const __bf16*)p.q, (const __bf16*)p.k, (const __bf16*)p.v, (const __bf16*)p.d_o, p.lse,
-                               p.Dbuf, p.total_tokens, p.n_groups, p.Hq, p.Hkv, p.scale, p.tab, 0);
-        // responses: their first rows qualify only under a prompt shorter than RS_SHORT
-        if (p.min_prompt_len < RS_SHORT && p.total_responses > 0)
-            hipLaunchKernelGGL(rowsum_short_rows_kernel,
-                               dim3((unsigned)(p.n_groups + p.total_responses), (unsigned)p.Hq), dim3(128), 0, s,
-                               (const __bf16*)p.q, (const __bf16*)p.k, (const __bf16*)p.v, (const __bf16*)p.d_o, p.lse,
-                               p.Dbuf, p.total_tokens, p.n_groups, p.Hq, p.Hkv, p.scale, p.tab, 1);
+        // exact D for the rows that see only a few keys (sp_edge.hip)
+        e = launch_short_rows(p, false, s);
+        if (e != hipSuccess) return e;
     }
     else
         hipLaunchKernelGGL(rowsum_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)p.d_o,

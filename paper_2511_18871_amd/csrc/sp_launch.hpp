@@ -56,6 +56,10 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s);
 hipError_t launch_fwd_f32(const Problem& p, hipStream_t s);
 hipError_t launch_bwd_f32(const Problem& p, hipStream_t s);
 hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s);
+// Rows that see at most EDGE_LEN keys are recomputed by the edge kernel (sp_edge.hip): D, and dQ, which
+// the dq pass then does not store.
+constexpr int EDGE_LEN = 64;
+hipError_t launch_short_rows(const Problem& p, bool with_dq, hipStream_t s);
 hipError_t launch_rope(const void* x, void* y, const int* tab, int64_t total_tokens, int H, int d, double base,
                        bool inverse, bool f32, hipStream_t s);
 hipError_t launch_logprob_fwd(const void* z, const int* y, float* logp, float* lse, const int* tab,

@@ -28,7 +28,10 @@ def random_workload(seed):
     return W.Workload(f"rand{seed}", groups, hq, hkv, 128, torch.bfloat16, 300 + seed)
 
 
-@pytest.mark.parametrize("seed", range(14))
+# 0..13: the first seeds of the generator.  The others are the seeds, of 1500 more drawn once, on which an
+# earlier version of the backward missed the max-abs gate by 1-23 % (dQ of rows with two or three keys, dK of
+# keys seen by two or three rows: the bf16 rounding of dS did not average out there).
+@pytest.mark.parametrize("seed", list(range(14)) + [360, 910, 1190, 1306, 1482])
 def test_random_packing_fwd_bwd(seed):
     w = random_workload(seed)
     t = W.make_tensors(w)
