@@ -264,7 +264,8 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
  * at prompt_len, so attention over the pack equals per-sample training including positions.
  * Half-split rotary form (the Qwen-family convention): theta_i = rope_base^(-2i/head_dim),
  * pair (x[i], x[i + head_dim/2]) of a token at position p turns by the angle p * theta_i
- * (angles are evaluated in double precision).
+ * (theta_i and the product are formed in double precision and reduced to [-pi, pi] before the
+ * fp32 sine and cosine).
  *   x, y          DEVICE [T_total, n_heads, head_dim], dtype elements; y may equal x (in place).
  *                 Call it on q (n_q_heads) and on k (n_kv_heads) before sp_attn_fwd; v is not rotated.
  *   inverse       0: rotate by +angle.  1: rotate by -angle, which turns the gradients that
@@ -278,6 +279,17 @@ sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
                        const int32_t* Gs, const int32_t* resp_lens_flat,
                        int32_t head_dim, double rope_base, sp_dtype dtype,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same rotation applied to q (n_q_heads) and to k (n_kv_heads) in ONE launch: one segment-table
+ * upload, one position lookup per token and one set of angles serve both tensors (with inverse = 1:
+ * dq and dk).  Results are bitwise those of two sp_attn_rope calls.  Arguments as sp_attn_rope; the
+ * workspace is that of the q call. */
+sp_status sp_attn_rope_qk(const void* q, void* q_out, int32_t n_q_heads,
+                          const void* k, void* k_out, int32_t n_kv_heads, int32_t inverse,
+                          int32_t n_groups, const int32_t* prompt_lens,
+                          const int32_t* Gs, const int32_t* resp_lens_flat,
+                          int32_t head_dim, double rope_base, sp_dtype dtype,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- Response-token loss (Section 4.3, modification 4; Section 2 objective) ------------------
  * The loss of the pack is a cross-entropy over its RESPONSE tokens; prompt rows are discarded.
@@ -345,6 +357,15 @@ sp_status sp_attn_segment_table(int32_t n_groups, const int32_t* prompt_lens, co
  * SP_ERR_INVALID_ARG for a NULL/misaligned pointer or a count < 1. */
 sp_status sp_attn_mfma_ceiling(int32_t lds_operands, const void* a, const void* b, int32_t iters,
                                int32_t n_blocks, float* out, void* stream);
+
+/* Tuning knob, process-wide (no counterpart in the paper).  The bf16 kernels come in two workgroup
+ * shapes: 256 query rows with one workgroup per CU, for long key loops, and 128 rows with two
+ * workgroups per CU, whose fixed per-workgroup costs overlap, for batches of short groups.  A call takes
+ * the small shape when a 256-row workgroup of its packing would run fewer than `steps` 64-key steps on
+ * average (host arithmetic on the lengths).  Default 40; 0 = always the large shape; a large value =
+ * always the small one; negative = back to the default.  Results do not depend on the shape beyond
+ * rounding order.  For measurements and tests; safe to call at any time between calls. */
+void sp_attn_set_small_shape_steps(int32_t steps);
 
 /* Text of the most recent error on the calling thread ("" if none).  The pointer
  * refers to thread-local static storage; the caller must not free it. */

@@ -22,9 +22,9 @@ SP_BWD_STAGE_ROWSUM, SP_BWD_STAGE_DKDV, SP_BWD_STAGE_DQ, SP_BWD_STAGE_ALL = 1, 2
 SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_reserve_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
-           "sp_attn_bwd_batched", "sp_attn_bwd_batched_static", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
+           "sp_attn_bwd_batched", "sp_attn_bwd_batched_static", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_rope_qk", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
            "sp_attn_loss_workspace_bytes", "sp_attn_logprob_fwd", "sp_attn_logprob_bwd", "sp_attn_grpo_loss",
-           "sp_attn_segment_table", "sp_attn_mfma_ceiling", "sp_attn_last_error", "sp_attn_version")
+           "sp_attn_segment_table", "sp_attn_mfma_ceiling", "sp_attn_set_small_shape_steps", "sp_attn_last_error", "sp_attn_version")
 
 _lib = None
 
@@ -87,10 +87,14 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_grpo_loss.argtypes = [vp, vp, vp, vp, f32, f32, f32, vp, vp, i32, ip, ip, ip, vp, sz, vp]
     lib.sp_attn_rope.restype = ctypes.c_int
     lib.sp_attn_rope.argtypes = [vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
+    lib.sp_attn_rope_qk.restype = ctypes.c_int
+    lib.sp_attn_rope_qk.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_segment_table.restype = ctypes.c_int
     lib.sp_attn_segment_table.argtypes = [i32, ip, ip, ip, ip, sz, ctypes.POINTER(sz)]
     lib.sp_attn_mfma_ceiling.restype = ctypes.c_int
     lib.sp_attn_mfma_ceiling.argtypes = [i32, vp, vp, i32, i32, vp, vp]
+    lib.sp_attn_set_small_shape_steps.restype = None
+    lib.sp_attn_set_small_shape_steps.argtypes = [i32]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
     lib.sp_attn_last_error.argtypes = []
     lib.sp_attn_version.restype = ctypes.c_char_p
@@ -335,6 +339,23 @@ def sp_attn_rope(x, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_fla
     return out
 
 
+def sp_attn_rope_qk(q, k, prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int], rope_base: float,
+                    inverse: bool = False, q_out=None, k_out=None, workspace=None, stream=None):
+    """Rotary embedding of q [T, Hq, d] and k [T, Hkv, d] in one launch; returns (q_out, k_out)."""
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    q_out = torch.empty_like(q) if q_out is None else q_out
+    k_out = torch.empty_like(k) if k_out is None else k_out
+    if workspace is None:
+        need = workspace_bytes(False, T, len(prompt_lens), len(resp_lens_flat), Hq, Hq, d, _dtype_code(q))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib.sp_attn_rope_qk(q.data_ptr(), q_out.data_ptr(), Hq, k.data_ptr(), k_out.data_ptr(), Hkv, int(inverse),
+                               len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), d, float(rope_base),
+                               _dtype_code(q), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return q_out, k_out
+
+
 def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Sequence[int],
                         resp_lens_flat: Sequence[int], softmax_scale: float, dq=None, dk=None, dv=None,
                         workspace=None, stream=None):
@@ -350,6 +371,11 @@ def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Se
                                    _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
                                    _dtype_code(q), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def set_small_shape_steps(steps: int) -> None:
+    """Threshold (mean 64-key steps per 256-row workgroup) below which calls take the 128-row kernel shape."""
+    load_library().sp_attn_set_small_shape_steps(steps)
 
 
 def sp_attn_mfma_ceiling(lds_operands: int, a, b, iters: int, out, n_blocks: int = 256, stream=None) -> float:

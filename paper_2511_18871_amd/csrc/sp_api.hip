@@ -18,6 +18,11 @@
 #define SP_STATIC_SCRATCH_BYTES_IMPL ((size_t)32 << 20)
 static __device__ __align__(256) unsigned char scratch[SP_STATIC_SCRATCH_BYTES_IMPL];
 
+namespace sp {
+namespace { std::atomic<int> g_small_steps{40}; }
+int small_shape_steps() { return g_small_steps.load(std::memory_order_relaxed); }
+}  // namespace sp
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -188,6 +193,7 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.o_lo_flag = (bwd && !o_lo && tag_mode == sp::TAG_CHECK) ? (const uint32_t*)workspace + sp::TAG_FLAG_WORD : nullptr;
     p.accumulate = (flags & SP_FLAG_ACCUMULATE_DKDV) != 0;
     p.host_group_tokens = L.group_tokens.data();
+    p.host_table = L.words.data();
 
     hipError_t e = keep_tag ? hipSuccess : sp::launch_reserve_tag((uint32_t*)workspace, tag, tag_mode, s);
     if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
@@ -329,6 +335,7 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
     p.total_responses = L.total_responses; p.min_prompt_len = L.min_prompt_len;
     p.Hq = n_q_heads; p.Hkv = n_kv_heads; p.head_dim = head_dim; p.scale = softmax_scale;
     p.host_group_tokens = L.group_tokens.data();
+    p.host_table = L.words.data();
     hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
     if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
     if (e == hipSuccess) {
@@ -348,14 +355,16 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
     return SP_OK;
 }
 
-sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse, int32_t n_groups,
-                       const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
-                       int32_t head_dim, double rope_base, sp_dtype dtype, void* workspace, size_t workspace_bytes,
-                       void* stream) {
+namespace {
+sp_status rope_call(const void* x, void* y, int32_t H, const void* x2, void* y2, int32_t H2, int32_t inverse,
+                    int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                    int32_t head_dim, double rope_base, sp_dtype dtype, void* workspace, size_t workspace_bytes,
+                    void* stream) {
     g_err[0] = 0;
-    if (!x || !y) return fail(SP_ERR_INVALID_ARG, "a tensor pointer is NULL");
-    if (misaligned(x) || misaligned(y)) return fail(SP_ERR_INVALID_ARG, "tensor pointer is not 16-byte aligned");
-    if (n_heads < 1) return fail(SP_ERR_INVALID_ARG, "n_heads=%d", n_heads);
+    if (!x || !y || (x2 && !y2)) return fail(SP_ERR_INVALID_ARG, "a tensor pointer is NULL");
+    if (misaligned(x) || misaligned(y) || misaligned(x2) || misaligned(y2))
+        return fail(SP_ERR_INVALID_ARG, "tensor pointer is not 16-byte aligned");
+    if (H < 1 || (x2 && H2 < 1)) return fail(SP_ERR_INVALID_ARG, "head counts %d, %d", H, H2);
     if (!(rope_base > 1.0) || !std::isfinite(rope_base))
         return fail(SP_ERR_INVALID_ARG, "rope_base must be finite and > 1");
     if (dtype != SP_BF16 && dtype != SP_F32) return fail(SP_ERR_UNSUPPORTED, "unknown dtype %d", (int)dtype);
@@ -363,8 +372,7 @@ sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
     Layout L;
     sp_status st = build_table(n_groups, prompt_lens, Gs, resp_lens_flat, L);
     if (st != SP_OK) return st;
-    const size_t need = sp_attn_workspace_bytes(0, L.total_tokens, n_groups, L.total_responses, n_heads, n_heads,
-                                                head_dim, dtype);
+    const size_t need = sp_attn_workspace_bytes(0, L.total_tokens, n_groups, L.total_responses, H, H, head_dim, dtype);
     if (!workspace || misaligned(workspace) || workspace_bytes < need)
         return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
                     workspace_bytes, need);
@@ -372,10 +380,28 @@ sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse,
     hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
     if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
     if (e == hipSuccess)
-        e = sp::launch_rope(x, y, table_of(workspace), L.total_tokens, n_heads, head_dim, rope_base, inverse != 0,
+        e = sp::launch_rope(x, y, H, x2, y2, H2, table_of(workspace), L.total_tokens, head_dim, rope_base, inverse != 0,
                             dtype == SP_F32, s);
     if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
     return SP_OK;
+}
+}  // namespace
+
+sp_status sp_attn_rope(const void* x, void* y, int32_t n_heads, int32_t inverse, int32_t n_groups,
+                       const int32_t* prompt_lens, const int32_t* Gs, const int32_t* resp_lens_flat,
+                       int32_t head_dim, double rope_base, sp_dtype dtype, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    return rope_call(x, y, n_heads, nullptr, nullptr, 0, inverse, n_groups, prompt_lens, Gs, resp_lens_flat, head_dim,
+                     rope_base, dtype, workspace, workspace_bytes, stream);
+}
+
+sp_status sp_attn_rope_qk(const void* q, void* q_out, int32_t n_q_heads, const void* k, void* k_out, int32_t n_kv_heads,
+                          int32_t inverse, int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
+                          const int32_t* resp_lens_flat, int32_t head_dim, double rope_base, sp_dtype dtype,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    if (!k || !k_out) { g_err[0] = 0; return fail(SP_ERR_INVALID_ARG, "a tensor pointer is NULL"); }
+    return rope_call(q, q_out, n_q_heads, k, k_out, n_kv_heads, inverse, n_groups, prompt_lens, Gs, resp_lens_flat,
+                     head_dim, rope_base, dtype, workspace, workspace_bytes, stream);
 }
 
 size_t sp_attn_loss_workspace_bytes(int64_t total_tokens, int32_t n_groups, int64_t total_responses) {
@@ -509,6 +535,10 @@ sp_status sp_attn_bwd_batched_static(const void* q, const void* k, const void* v
                     "with a workspace): %.300s", (size_t)SP_STATIC_SCRATCH_BYTES, msg);
     }
     return st;
+}
+
+void sp_attn_set_small_shape_steps(int32_t steps) {
+    sp::g_small_steps.store(steps < 0 ? 40 : steps, std::memory_order_relaxed);
 }
 
 const char* sp_attn_last_error(void) { return g_err; }

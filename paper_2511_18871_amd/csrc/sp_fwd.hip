@@ -50,11 +50,19 @@ struct FwdArgs {
 // reference point m the row had before the tile (see `step`).  Two steps run per workgroup
 // barrier; the K and V tiles of the following two steps are copied into LDS meanwhile.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
-    constexpr int BM = 256;
+//
+// Two shapes of workgroup.  NW = 8: 256 rows, four K and four V buffers (128 KB of LDS), one workgroup
+// per CU: the shape for long key loops.  NW = 4: 128 rows, two K and two V buffers (64 KB), one step
+// per barrier, TWO workgroups per CU: each workgroup's fixed costs (table lookups, first loads,
+// epilogue, the gap before the next dispatch) then overlap with the other's key loop, which is what
+// batches of short groups need, where a workgroup runs only a handful of steps.
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // two waves per SIMD in either shape
+    constexpr int BM = 32 * NW;
+    constexpr int NB = NW == 8 ? 4 : 2;            // K buffers = V buffers
     constexpr int RD = 3;      // LDS operand ring depth (prefetch distance RD - 1 MFMAs)
-    __shared__ __attribute__((aligned(1024))) char ldsKb[4][TILE_BYTES];      // K tile t lives in ldsKb[t & 3]
-    __shared__ __attribute__((aligned(1024))) char ldsVb[4][TILE_BYTES];      // V tile t in ldsVb[t & 3]
+    __shared__ __attribute__((aligned(1024))) char ldsKb[NB][TILE_BYTES];      // K tile t lives in ldsKb[t % NB]
+    __shared__ __attribute__((aligned(1024))) char ldsVb[NB][TILE_BYTES];      // V tile t in ldsVb[t % NB]
 
     // blocks are dealt set-major; blocks_per_set is a multiple of 8, so the block -> XCD mapping
     // of a set does not depend on how many sets the launch carries
@@ -148,8 +156,9 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)p);
     };
     const unsigned chunk0 = 4096u * (w & 3);
-    const unsigned m0K[4] = {lds_u32(ldsKb[0]) + chunk0, lds_u32(ldsKb[1]) + chunk0, lds_u32(ldsKb[2]) + chunk0, lds_u32(ldsKb[3]) + chunk0};
-    const unsigned m0V[4] = {lds_u32(ldsVb[0]) + chunk0, lds_u32(ldsVb[1]) + chunk0, lds_u32(ldsVb[2]) + chunk0, lds_u32(ldsVb[3]) + chunk0};
+    unsigned m0K[NB], m0V[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) { m0K[b] = lds_u32(ldsKb[b]) + chunk0; m0V[b] = lds_u32(ldsVb[b]) + chunk0; }
     auto issue = [&](uint64_t base_s, unsigned m0dst, int it) {
         if (!copier || it >= total) return;
         const int kt = tile_at(it);
@@ -254,8 +263,8 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     // the row sum, and recomputes this tile's P -- a rare path, taken a few times per row.
     auto step = [&](int j, auto par_tag, f32x16 (&Scur)[2], f32x16 (&Snext)[2], const unsigned (&pbw)[16], unsigned (&pnew)[16]) {
         constexpr int R = decltype(par_tag)::value;
-        const char* ldsV = ldsVb[(R + 3) & 3];  // V(j-1)
-        const char* ldsK = ldsKb[(R + 1) & 3];  // K(j+1)
+        const char* ldsV = ldsVb[(R + NB - 1) % NB];  // V(j-1)
+        const char* ldsK = ldsKb[(R + 1) % NB];       // K(j+1)
         if (needs_mask(j)) mask(j, Scur);
         __builtin_amdgcn_sched_barrier(0);
         const float mc = m * cs;
@@ -330,19 +339,24 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         lsr += tsr;
     };
 
-    // Zero-fill every V buffer that is multiplied against P = 0 before a copy has filled it: buffer 3
-    // stands for V(-1) in the first step, and a key loop of fewer than three tiles is still padded to
-    // four steps, whose V(1), V(2) are never copied.  LDS keeps what earlier workgroups left there (bit
-    // patterns that may read as inf or NaN), and 0 * NaN would reach O.
+    // Zero-fill every V buffer that is multiplied against P = 0 before a copy has filled it: the last
+    // buffer stands for V(-1) in the first step, and a key loop shorter than the buffer ring is still
+    // padded to a whole turn of it, whose later V tiles are never copied.  LDS keeps what earlier
+    // workgroups left there (bit patterns that may read as inf or NaN), and 0 * NaN would reach O.
 #pragma unroll
-    for (int b = 1; b < 4; ++b)
-        if (b == 3 || total <= b)
-            for (int i = tid; i < TILE_BYTES / 16; i += 512)
+    for (int b = 1; b < NB; ++b)
+        if (b == NB - 1 || total <= b)
+            for (int i = tid; i < TILE_BYTES / 16; i += 64 * NW)
                 reinterpret_cast<i32x4*>(ldsVb[b])[i] = i32x4{0, 0, 0, 0};
-    issue(kbase_s, m0K[0], 0);
-    issue(kbase_s, m0K[1], 1);
-    issue(kbase_s, m0K[2], 2);
-    issue(vbase_s, m0V[0], 0);
+    if constexpr (NB == 4) {
+        issue(kbase_s, m0K[0], 0);
+        issue(kbase_s, m0K[1], 1);
+        issue(kbase_s, m0K[2], 2);
+        issue(vbase_s, m0V[0], 0);
+    } else {
+        issue(kbase_s, m0K[0], 0);
+        issue(kbase_s, m0K[1], 1);
+    }
     wait_vm0();
     __syncthreads();
     qk_plain(ldsKb[0], sA);
@@ -359,40 +373,59 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
         // -126 / log2(e) underflow to a zero sum.)
         m = (mx == -INFINITY) ? M_NONE : mx;
     }
-    // Two steps per workgroup barrier: with four K and four V buffers the tiles of the next two
-    // steps are copied while these two run.  At the barrier before steps j, j+1 (j even) the tiles
-    // V(j-1), V(j), K(j+1), K(j+2) are resident and V(j+1), V(j+2), K(j+3), K(j+4) are issued into
-    // the four buffers that the previous two steps read last.  The loop is padded to a multiple of
-    // four steps (buffer indices are compile-time); padded steps are fully masked.
-    const int total4 = (total + 3) & ~3;
-    for (int j = 0; j < total4; j += 4) {
-        wait_vm0();
-        __syncthreads();
-        issue(vbase_s, m0V[1], j + 1);
-        issue(vbase_s, m0V[2], j + 2);
-        issue(kbase_s, m0K[3], j + 3);
-        issue(kbase_s, m0K[0], j + 4);
-        step(j, std::integral_constant<int, 0>{}, sA, sB, pbA, pbB);
-        step(j + 1, std::integral_constant<int, 1>{}, sB, sA, pbB, pbA);
-        wait_vm0();
-        __syncthreads();
-        issue(vbase_s, m0V[3], j + 3);
-        issue(vbase_s, m0V[0], j + 4);
-        issue(kbase_s, m0K[1], j + 5);
-        issue(kbase_s, m0K[2], j + 6);
-        step(j + 2, std::integral_constant<int, 2>{}, sA, sB, pbA, pbB);
-        step(j + 3, std::integral_constant<int, 3>{}, sB, sA, pbB, pbA);
+    if constexpr (NB == 4) {
+        // Two steps per workgroup barrier: with four K and four V buffers the tiles of the next two
+        // steps are copied while these two run.  At the barrier before steps j, j+1 (j even) the tiles
+        // V(j-1), V(j), K(j+1), K(j+2) are resident and V(j+1), V(j+2), K(j+3), K(j+4) are issued into
+        // the four buffers that the previous two steps read last.  The loop is padded to a multiple of
+        // four steps (buffer indices are compile-time); padded steps are fully masked.
+        const int total4 = (total + 3) & ~3;
+        for (int j = 0; j < total4; j += 4) {
+            wait_vm0();
+            __syncthreads();
+            issue(vbase_s, m0V[1], j + 1);
+            issue(vbase_s, m0V[2], j + 2);
+            issue(kbase_s, m0K[3], j + 3);
+            issue(kbase_s, m0K[0], j + 4);
+            step(j, std::integral_constant<int, 0>{}, sA, sB, pbA, pbB);
+            step(j + 1, std::integral_constant<int, 1>{}, sB, sA, pbB, pbA);
+            wait_vm0();
+            __syncthreads();
+            issue(vbase_s, m0V[3], j + 3);
+            issue(vbase_s, m0V[0], j + 4);
+            issue(kbase_s, m0K[1], j + 5);
+            issue(kbase_s, m0K[2], j + 6);
+            step(j + 2, std::integral_constant<int, 2>{}, sA, sB, pbA, pbB);
+            step(j + 3, std::integral_constant<int, 3>{}, sB, sA, pbB, pbA);
+        }
+    } else {
+        // One step per barrier.  At the barrier before step j the tiles V(j-1) and K(j+1) are resident
+        // (issued a whole step earlier); V(j) and K(j+2) are issued into the buffers that step j-1 read
+        // last (V(j-2), and K(j), from which S(j) has been formed).  Padded to an even count of steps.
+        const int total2 = (total + 1) & ~1;
+        for (int j = 0; j < total2; j += 2) {
+            wait_vm0();
+            __syncthreads();
+            issue(vbase_s, m0V[0], j);
+            issue(kbase_s, m0K[0], j + 2);
+            step(j, std::integral_constant<int, 0>{}, sA, sB, pbA, pbB);
+            wait_vm0();
+            __syncthreads();
+            issue(vbase_s, m0V[1], j + 1);
+            issue(kbase_s, m0K[1], j + 3);
+            step(j + 1, std::integral_constant<int, 1>{}, sB, sA, pbB, pbA);
+        }
     }
     wait_vm0();
     __syncthreads();
-    pv_plain(ldsVb[3], pbA);                    // P of step total4 - 1, V(total4 - 1)
+    pv_plain(ldsVb[NB - 1], pbA);               // P of the last (padded) step and its V tile
 
     // O is normalised by the sum of the ROUNDED weights, the ones V was actually multiplied by:
     // a row dominated by one key then returns that key's V exactly, whatever the reference point.
     // LSE uses the unrounded sum.
     const float ltot = pair_sum(lsum);
     const float lrt = pair_sum(lsr);
-    // The K buffers are free from here on (every wave has passed the last barrier and only ldsVb[3]
+    // The K buffers are free from here on (every wave has passed the last barrier and only the last V buffer
     // is still read).  A lane holds 16 pieces of 8 bytes of its row; written to memory directly, one
     // store instruction would touch 32 rows.  Each wave therefore stages its own 32 rows x 256 B in
     // its own 8 KB of LDS (swizzled like the operand tiles: two-way conflicts on the 8-byte writes,
@@ -435,6 +468,31 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
 
 }  // namespace
 
+// Mean number of 64-key steps that a 256-row workgroup of this packing runs (host arithmetic on the
+// segment table): the measure by which the workgroup shape is chosen.
+static double mean_key_steps(const Problem& p) {
+    const int32_t* tab = p.host_table;
+    int64_t steps = 0, tiles = 0;
+    for (int g = 0; g < p.n_groups; ++g) {
+        const int32_t* e = tab + TAB_HEADER + TAB_GROUP_WORDS * g;
+        const int Lp = e[1], Tg = e[2], G = e[4];
+        const int32_t* roff = tab + e[3];
+        for (int t0 = 0; t0 < Tg; t0 += 256, ++tiles) {
+            const int t1 = t0 + 256 < Tg ? t0 + 256 : Tg;
+            const int n1 = ((Lp < t1 ? Lp : t1) + BN - 1) / BN;
+            steps += n1;
+            if (t1 > Lp) {
+                const int first = t0 > Lp ? t0 : Lp;          // first response row: its segment start opens the range
+                int lo = 0, hi = G;
+                while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (roff[mid] <= first) lo = mid; else hi = mid; }
+                const int k2b = roff[lo] / BN > n1 ? roff[lo] / BN : n1;
+                steps += (t1 + BN - 1) / BN - k2b;
+            }
+        }
+    }
+    return tiles ? (double)steps / (double)tiles : 0.0;
+}
+
 hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
     FwdArgs a{};
     const int n_sets = p.n_sets > 1 ? p.n_sets : 1;
@@ -447,10 +505,15 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
     a.tab = p.tab; a.n_groups = p.n_groups;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive; a.resp_only = p.resp_only;
     a.o_lo = n_sets == 1 ? (__bf16*)p.o_lo_out : nullptr;
-    a.n_tiles = count_tiles(p, 256);
+    // Short key loops: the 128-row shape, two workgroups per CU (see fwd_kernel).  The naive baseline keeps
+    // the 256-row shape whatever the packing (its loops are long by construction).
+    const bool small = !p.naive && mean_key_steps(p) < (double)small_shape_steps();
+    const int bm = small ? 128 : 256;
+    a.n_tiles = count_tiles(p, bm);
     a.blocks_per_set = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
     if (a.blocks_per_set % 8 != 0) a.blocks_per_set += 8 - a.blocks_per_set % 8;
-    hipLaunchKernelGGL(fwd_kernel, dim3(a.blocks_per_set * n_sets), dim3(512), 0, s, a);
+    if (small) hipLaunchKernelGGL(fwd_kernel<4>, dim3(a.blocks_per_set * n_sets), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(fwd_kernel<8>, dim3(a.blocks_per_set * n_sets), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 

@@ -47,8 +47,10 @@ struct Problem {
     const uint32_t* o_lo_flag;                            // device word: o_lo may be used only if it is non-zero (NULL: always)
     int accumulate;                                       // backward: dk, dv += instead of =
     float* dkdv_partial;                                  // bf16 backward on small problems: fp32 per-q-head partials
-    // host copies of the per-group token counts, for grid sizing
+    // host copies of the per-group token counts and of the whole segment table, for grid sizing and
+    // for choosing kernel shapes
     const int* host_group_tokens;
+    const int32_t* host_table;
 };
 
 hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s);
@@ -60,8 +62,8 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s);
 // the dq pass then does not store.
 constexpr int EDGE_LEN = 64;
 hipError_t launch_short_rows(const Problem& p, bool with_dq, hipStream_t s);
-hipError_t launch_rope(const void* x, void* y, const int* tab, int64_t total_tokens, int H, int d, double base,
-                       bool inverse, bool f32, hipStream_t s);
+hipError_t launch_rope(const void* x, void* y, int H, const void* x2, void* y2, int H2, const int* tab,
+                       int64_t total_tokens, int d, double base, bool inverse, bool f32, hipStream_t s);
 hipError_t launch_logprob_fwd(const void* z, const int* y, float* logp, float* lse, const int* tab,
                               int64_t total_tokens, int64_t V, bool f32, hipStream_t s);
 hipError_t launch_logprob_bwd(const void* z, const int* y, const float* lse, const float* g, void* dz,
@@ -71,6 +73,10 @@ hipError_t launch_grpo(const float* logp, const float* old, const float* ref, co
                        float eps_high, float beta, hipStream_t s);
 hipError_t launch_reserve_tag(uint32_t* tag_block, const ReserveTag& tag, int mode, hipStream_t s);
 hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s);
+
+// Packings whose 256-row workgroups would run fewer 64-key steps than this on average take the kernels'
+// 128-row shape (two workgroups per CU).  SP_ATTN_SMALL_STEPS overrides the default, for measurements.
+int small_shape_steps();
 
 inline int count_tiles(const Problem& p, int bm) {
     int n = 0;

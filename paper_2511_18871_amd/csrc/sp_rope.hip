@@ -6,11 +6,15 @@
 // maps gradients with respect to rotated q / k back to gradients with respect to q / k.
 //
 // The kernel is a pure HBM pass (read x, write y).  A thread owns 8 consecutive pair indices of
-// one token (two 16-byte loads per head for bf16), computes their 8 angles once in double
-// precision (positions reach tens of thousands of radians, where an fp32 angle is already off by
-// 1e-3) and applies them to every head of the token.
+// one token (two 16-byte loads per head for bf16) and evaluates their 8 angles once: the frequencies
+// theta_i come from the host in double precision (a kernel argument), the product p * theta_i is
+// formed and reduced to [-pi, pi] in double (positions reach tens of thousands of radians, where an
+// fp32 product is already off by 1e-3), and only the reduced angle goes through the fp32 sine and
+// cosine.  The same angles then serve every head of the token -- of one tensor, or of q AND k in one
+// launch (sp_attn_rope_qk): one table upload, one position lookup and one set of angles for both.
 #include "sp_common.hpp"
 #include "sp_launch.hpp"
+#include <cmath>
 
 namespace sp {
 namespace {
@@ -19,10 +23,12 @@ template <typename T> struct Vec8;
 template <> struct Vec8<__bf16> { typedef bf16x8 type; };
 template <> struct Vec8<float> { typedef float type __attribute__((ext_vector_type(8))); };
 
+struct RopeFreq { double theta[64]; };      // theta_i = base^(-2 i / d), i < d / 2 <= 64
+
 template <typename T>
-__global__ __launch_bounds__(256) void rope_kernel(const T* __restrict__ x, T* __restrict__ y,
-                                                   const int* __restrict__ tab, int H, int d,
-                                                   double log2_base, int inverse) {
+__global__ __launch_bounds__(256) void rope_kernel(const T* __restrict__ x, T* __restrict__ y, int H,
+                                                   const T* __restrict__ x2, T* __restrict__ y2, int H2,
+                                                   const int* __restrict__ tab, int d, RopeFreq f, int inverse) {
     typedef typename Vec8<T>::type V8;
     const int half = d >> 1;
     const int tpt = half >> 3;                          // threads per token
@@ -38,43 +44,49 @@ __global__ __launch_bounds__(256) void rope_kernel(const T* __restrict__ x, T* _
     float c[8], s[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const double theta = exp2(-2.0 * (double)(i0 + e) / (double)d * log2_base);
-        double sv, cv;
-        sincos((double)pos * theta, &sv, &cv);
-        c[e] = (float)cv;
-        s[e] = (float)(inverse ? -sv : sv);
+        const double ang = (double)pos * f.theta[i0 + e];
+        const double red = ang - 6.283185307179586476925 * rint(ang * 0.15915494309189533577);   // into [-pi, pi]
+        float sv, cv;
+        sincosf((float)red, &sv, &cv);
+        c[e] = cv;
+        s[e] = inverse ? -sv : sv;
     }
-    const T* xr = x + tok * (int64_t)H * d + i0;
-    T* yr = y + tok * (int64_t)H * d + i0;
-    for (int h = 0; h < H; ++h) {
-        const V8 lo = *reinterpret_cast<const V8*>(xr + (int64_t)h * d);
-        const V8 hi = *reinterpret_cast<const V8*>(xr + (int64_t)h * d + half);
-        V8 ylo, yhi;
+    auto rotate = [&](const T* __restrict__ xin, T* __restrict__ yout, int heads) {
+        const T* xr = xin + tok * (int64_t)heads * d + i0;
+        T* yr = yout + tok * (int64_t)heads * d + i0;
+        for (int h = 0; h < heads; ++h) {
+            const V8 lo = *reinterpret_cast<const V8*>(xr + (int64_t)h * d);
+            const V8 hi = *reinterpret_cast<const V8*>(xr + (int64_t)h * d + half);
+            V8 ylo, yhi;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float a = (float)lo[e], b = (float)hi[e];
-            ylo[e] = (T)(a * c[e] - b * s[e]);
-            yhi[e] = (T)(a * s[e] + b * c[e]);
+            for (int e = 0; e < 8; ++e) {
+                const float a = (float)lo[e], b = (float)hi[e];
+                ylo[e] = (T)(a * c[e] - b * s[e]);
+                yhi[e] = (T)(a * s[e] + b * c[e]);
+            }
+            *reinterpret_cast<V8*>(yr + (int64_t)h * d) = ylo;
+            *reinterpret_cast<V8*>(yr + (int64_t)h * d + half) = yhi;
         }
-        *reinterpret_cast<V8*>(yr + (int64_t)h * d) = ylo;
-        *reinterpret_cast<V8*>(yr + (int64_t)h * d + half) = yhi;
-    }
+    };
+    rotate(x, y, H);
+    if (x2) rotate(x2, y2, H2);
 }
 
 }  // namespace
 
-hipError_t launch_rope(const void* x, void* y, const int* tab, int64_t total_tokens, int H, int d,
-                       double base, bool inverse, bool f32, hipStream_t s) {
+hipError_t launch_rope(const void* x, void* y, int H, const void* x2, void* y2, int H2, const int* tab,
+                       int64_t total_tokens, int d, double base, bool inverse, bool f32, hipStream_t s) {
     const int tpt = d / 16;
     const int64_t threads = total_tokens * tpt;
     const int grid = (int)((threads + 255) / 256);
-    const double l2b = log2(base);
+    RopeFreq f{};
+    for (int i = 0; i < d / 2; ++i) f.theta[i] = pow(base, -2.0 * (double)i / (double)d);
     if (f32)
-        hipLaunchKernelGGL(rope_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, (float*)y, tab, H, d, l2b,
-                           (int)inverse);
+        hipLaunchKernelGGL(rope_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, (float*)y, H,
+                           (const float*)x2, (float*)y2, H2, tab, d, f, (int)inverse);
     else
-        hipLaunchKernelGGL(rope_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)x, (__bf16*)y, tab, H, d,
-                           l2b, (int)inverse);
+        hipLaunchKernelGGL(rope_kernel<__bf16>, dim3(grid), dim3(256), 0, s, (const __bf16*)x, (__bf16*)y, H,
+                           (const __bf16*)x2, (__bf16*)y2, H2, tab, d, f, (int)inverse);
     return hipGetLastError();
 }
 

@@ -106,7 +106,7 @@ def useful_flops(w: Workload, backward: bool) -> float:
 
 
 def config(idx: int) -> Workload:
-    """The five benchmark configurations (1-based)."""
+    """The five benchmark configurations (1-based) and two more workloads of many short groups."""
     if idx == 1:
         return Workload("c1_tiny_fp32", [Group(64, [32] * 4)], 2, 2, 64, torch.float32, 1000)
     if idx == 2:
@@ -122,6 +122,23 @@ def config(idx: int) -> Workload:
         groups = [Group(16384, ragged_lengths(5000, 32, 64, 256))]
         return Workload("c5_extreme_sharing", groups, 40, 8, 128, torch.bfloat16, 5000,
                         stress_k_fraction=0.01, stress_k_scale=8.0)
+    if idx == 6:
+        # The shape of the paper's own shared-prompt experiment (Table 3: a 7B model of the Qwen2.5 family,
+        # grade-school maths prompts, 1K context per sample, 16 of the 32 rollouts of a prompt in one
+        # micro-batch): many groups, each a short prompt and 16 responses of a few hundred tokens.
+        # Lengths are seeded stand-ins for that distribution, not dataset items.
+        groups = []
+        for g in range(64):
+            lp = ragged_lengths(6000 + g, 1, 64, 192)[0]
+            groups.append(Group(lp, ragged_lengths(6500 + g, 16, 96, 416)))
+        return Workload("c6_table3_shape", groups, 28, 4, 128, torch.bfloat16, 6000)
+    if idx == 7:
+        # 64 groups of 1000 tokens: a prompt of about 70 % and four ragged responses (short-group regime)
+        groups = []
+        for g in range(64):
+            lens = ragged_lengths(9000 + g, 4, 40, 111)
+            groups.append(Group(1000 - sum(lens), lens))
+        return Workload("c7_short_groups_64x1000", groups, 32, 8, 128, torch.bfloat16, 7000)
     raise ValueError(f"no config {idx}")
 
 

@@ -113,3 +113,16 @@ def test_multi_set_forward_equals_separate_calls_and_oracle(dtype, d):
     o0, l0 = B.sp_attn_fwd_multi(qs[:1], ks[:1], vs[:1], w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale)
     torch.cuda.synchronize()
     assert torch.equal(o0[0], os[0]) and torch.equal(l0[0], lses[0])
+
+
+@pytest.mark.parametrize("steps", [0, 1 << 20])
+def test_both_workgroup_shapes_match_oracle(steps):
+    """The 256-row and the 128-row kernel shapes, each forced on a packing that spans several tiles of
+    either size (the library would pick by the mean length of the key loop)."""
+    w = W.small_ragged(seed=31, n_q_heads=6, n_kv_heads=2,
+                       groups=[W.Group(333, [1, 63, 65, 0, 127, 129, 200]), W.Group(70, [300, 5]), W.Group(0, [129])])
+    try:
+        B.set_small_shape_steps(steps)
+        check_full(w)
+    finally:
+        B.set_small_shape_steps(-1)

@@ -79,3 +79,24 @@ def test_rope_attention_chain_matches_oracle(dtype, d):
     gate("dQ", to64(dq), rdq, dtype)
     gate("dK", to64(dk), rdk, dtype)
     gate("dV", to64(dv), rdv, dtype)
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_rope_of_q_and_k_in_one_launch_equals_two_passes(dtype, d):
+    w = W.Workload("rope_qk", GROUPS, 6, 2, d, dtype, 57)
+    t = W.make_tensors(w)
+    q, k = t.q.cuda(), t.k.cuda()
+    pk = (w.prompt_lens(), w.Gs(), w.resp_lens_flat(), 1e6)
+    for inverse in (False, True):
+        q1, k1 = B.sp_attn_rope(q, *pk, inverse=inverse), B.sp_attn_rope(k, *pk, inverse=inverse)
+        q2, k2 = B.sp_attn_rope_qk(q, k, *pk, inverse=inverse)
+        torch.cuda.synchronize()
+        assert torch.equal(q1, q2) and torch.equal(k1, k2)
+    # in place, and back: the inverse rotation returns the input to rounding
+    qq, kk = q.clone(), k.clone()
+    B.sp_attn_rope_qk(qq, kk, *pk, q_out=qq, k_out=kk)
+    B.sp_attn_rope_qk(qq, kk, *pk, inverse=True, q_out=qq, k_out=kk)
+    torch.cuda.synchronize()
+    tol = 3e-2 if dtype == torch.bfloat16 else 1e-5
+    assert float((qq.float() - q.float()).abs().max()) <= tol * float(q.float().abs().max())
+    assert float((kk.float() - k.float()).abs().max()) <= tol * float(k.float().abs().max())
