@@ -103,6 +103,11 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="overwrite a 1 GiB buffer before every step so that L2 and the Infinity Cache hold none of "
                          "the inputs; throughput is then taken from the summed stage times, not the wall clock")
+    ap.add_argument("--no-reserve", action="store_true",
+                    help="give the calls a workspace without room for the forward-to-backward reserve (the backward then "
+                         "forms D from the bf16 o alone): measures what the reserve costs")
+    ap.add_argument("--probe-atomics", action="store_true",
+                    help="also measure the fp32 atomic-add rate that a one-pass backward's dQ accumulation would need")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -144,8 +149,8 @@ def main():
     lse = torch.empty(Hq, T, dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     # one workspace for the forward and the backward, with room for the forward-to-backward reserve
-    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, Hkv, d, code) + B.reserve_bytes(T, Hq, d, code),
-                     dtype=torch.uint8, device=dev)
+    ws = torch.empty(B.workspace_bytes(True, T, len(pl), len(rl), Hq, Hkv, d, code)
+                     + (0 if args.no_reserve else B.reserve_bytes(T, Hq, d, code)), dtype=torch.uint8, device=dev)
     do_bwd = w.backward
 
     stage_names = ["fwd"] + (["bwd_rowsum", "bwd_dq", "bwd_dkdv"] if do_bwd else [])
@@ -214,6 +219,8 @@ def main():
     }
     if flush is not None:
         out["cold_cache"] = True
+    if args.no_reserve:
+        out["reserve"] = False
     if do_bwd:
         bwd_ms = stage_ms["bwd_rowsum"] + stage_ms["bwd_dkdv"] + stage_ms["bwd_dq"]
         bwd_tf = bwd_flops / (bwd_ms * 1e-3) / 1e12
@@ -380,6 +387,28 @@ def main():
         out["rope"] = {"ms": round(rms, 4), "two_launches_ms": round(rms2, 4), "bytes": nbytes, "bound": "hbm",
                        "achieved": round(nbytes / (rms * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
                        "frac": round(nbytes / (rms * 1e-3) / 8e12, 4)}
+
+    if args.probe_atomics:
+        # the one-pass backward's dQ accumulation, alone: fp32 atomic adds of 64 x 128 tiles into [T, Hq, 128]
+        rows = (T + 63) // 64 * 64
+        acc = torch.zeros(rows * Hq * 128, dtype=torch.float32, device=dev)
+        res = {}
+        for name, layout in (("row_contiguous", 0), ("accumulator_scatter", 1)):
+            B.sp_attn_probe_atomic_add(acc, rows, Hq, 20, layout=layout)
+            eva = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            eva[0].record()
+            nb = B.sp_attn_probe_atomic_add(acc, rows, Hq, 1000 if layout == 0 else 200, layout=layout)
+            eva[1].record()
+            torch.cuda.synchronize()
+            res[name] = round(nb / (eva[0].elapsed_time(eva[1]) * 1e-3) / 1e9, 1)
+        pairs_hq = fwd_flops / (4.0 * d)
+        need = 4.0 * pairs_hq
+        out["atomic_add_probe"] = {"unit": "GB/s", **res, "one_pass_dq_bytes": need,
+                                   "one_pass_dq_ms_at_best_rate": round(need / (max(res.values()) * 1e9) * 1e3, 2),
+                                   "note": "fp32 atomic adds a one-pass backward would issue for dQ (4 bytes per allowed "
+                                           "pair and q head) against this box's measured rate; the dq pass takes "
+                                           f"{stage_ms.get('bwd_dq', 0.0):.2f} ms"}
+        del acc
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

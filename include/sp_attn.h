@@ -140,20 +140,22 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v,
                               float softmax_scale, sp_dtype dtype,
                               void* workspace, size_t workspace_bytes, void* stream);
 
-/* The backward runs in three stages that a caller may enqueue separately, e.g. to time
- * them or to overlap the two gradient passes on two streams:
- *   SP_BWD_STAGE_ROWSUM  D[h, t] = sum_j d_o[t,h,j] * o[t,h,j] and lse * log2(e) -> workspace
- *                        (needs o, d_o, lse; on the bf16 path also q, k, v: rows that see at
- *                        most 64 keys get D from its definition sum_s P*dP instead, because
- *                        the rounding of o weighs most on dq where a row has few keys)
+/* The backward runs in three stages that a caller may enqueue separately, e.g. to time them:
+ *   SP_BWD_STAGE_ROWSUM  D[h, t] = sum_j d_o[t,h,j] * o[t,h,j] (o plus the forward's rounding residual
+ *                        when the workspace holds a valid reserve or o_lo is given) and
+ *                        lse * log2(e) -> workspace.  Needs o, d_o, lse; on the bf16 path also q, k, v:
+ *                        rows that see at most 64 keys get D from its definition sum_s P*dP in fp32.
  *   SP_BWD_STAGE_DQ      dq      (needs D in the same workspace; o unused).  On the bf16 path it
- *                        also replaces D in the workspace by sum_s P*dP, the same quantity
- *                        evaluated in fp32 without the bf16 rounding of o.
+ *                        also REPLACES D in the workspace by sum_s P*dP, the same quantity
+ *                        evaluated in fp32 without the bf16 rounding of o, and writes the dq of rows
+ *                        that see at most 64 keys in a separate small kernel (fp32 dS).
  *   SP_BWD_STAGE_DKDV    dk, dv  (needs D in the same workspace; o unused)
- * Both gradient stages must be ordered after ROWSUM on the same workspace.  They may run in
- * either order, but DKDV is more accurate (and the pair is bitwise repeatable) when it is
- * ordered after DQ, which is what sp_attn_bwd* do.  Output pointers of stages that are not
- * requested may be NULL.
+ * Ordering on one workspace: ROWSUM first; then DQ and DKDV one after the other, never concurrently
+ * (DQ rewrites the D plane that DKDV reads: overlapping them, e.g. on two streams, is a data race).
+ * Either order of the two is correct; DKDV after DQ, which is what sp_attn_bwd* do, is the more
+ * accurate one when no reserve is used, and the only one whose results are bitwise repeatable from
+ * run to run.  To overlap the two gradient passes, give each its own workspace and run ROWSUM on
+ * both.  Output pointers of stages that are not requested may be NULL.
  * sp_attn_bwd_batched(...) is this call with SP_BWD_STAGE_ALL. */
 #define SP_BWD_STAGE_ROWSUM 1u
 #define SP_BWD_STAGE_DKDV   2u
@@ -357,6 +359,17 @@ sp_status sp_attn_segment_table(int32_t n_groups, const int32_t* prompt_lens, co
  * SP_ERR_INVALID_ARG for a NULL/misaligned pointer or a count < 1. */
 sp_status sp_attn_mfma_ceiling(int32_t lds_operands, const void* a, const void* b, int32_t iters,
                                int32_t n_blocks, float* out, void* stream);
+
+/* Measurement aid (no counterpart in the paper): the rate at which this chip adds 64 x 128 fp32 tiles
+ * into a [rows, heads, 128] fp32 accumulator with memory atomics -- what a backward that produced dQ, dK
+ * and dV in one pass would have to do for every (key tile, row tile, q head), 4 bytes per allowed pair
+ * and q head.  The two-pass backward of this library exists because of the figure this returns.
+ *   buf      DEVICE float[rows * heads * 128], rows a multiple of 64; its contents are added to
+ *   steps    tiles added per workgroup;  n_blocks  workgroups of 512 threads
+ *   layout   0: half-waves cover 128 contiguous bytes of a row; 1: lanes scatter as an MFMA accumulator
+ * Adds n_blocks * steps * 32768 bytes.  Asynchronous on `stream`; SP_ERR_INVALID_ARG for bad counts. */
+sp_status sp_attn_probe_atomic_add(float* buf, int64_t rows, int32_t heads, int32_t steps, int32_t n_blocks,
+                                   int32_t layout, void* stream);
 
 /* Tuning knob, process-wide (no counterpart in the paper).  The bf16 kernels come in two workgroup
  * shapes: 256 query rows with one workgroup per CU, for long key loops, and 128 rows with two

@@ -24,7 +24,7 @@ SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_reserve_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
            "sp_attn_bwd_batched", "sp_attn_bwd_batched_static", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_rope_qk", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
            "sp_attn_loss_workspace_bytes", "sp_attn_logprob_fwd", "sp_attn_logprob_bwd", "sp_attn_grpo_loss",
-           "sp_attn_segment_table", "sp_attn_mfma_ceiling", "sp_attn_set_small_shape_steps", "sp_attn_last_error", "sp_attn_version")
+           "sp_attn_segment_table", "sp_attn_mfma_ceiling", "sp_attn_probe_atomic_add", "sp_attn_set_small_shape_steps", "sp_attn_last_error", "sp_attn_version")
 
 _lib = None
 
@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_segment_table.argtypes = [i32, ip, ip, ip, ip, sz, ctypes.POINTER(sz)]
     lib.sp_attn_mfma_ceiling.restype = ctypes.c_int
     lib.sp_attn_mfma_ceiling.argtypes = [i32, vp, vp, i32, i32, vp, vp]
+    lib.sp_attn_probe_atomic_add.restype = ctypes.c_int
+    lib.sp_attn_probe_atomic_add.argtypes = [vp, i64, i32, i32, i32, i32, vp]
     lib.sp_attn_set_small_shape_steps.restype = None
     lib.sp_attn_set_small_shape_steps.argtypes = [i32]
     lib.sp_attn_last_error.restype = ctypes.c_char_p
@@ -371,6 +373,14 @@ def sp_attn_bwd_batched(q, k, v, o, lse, d_o, prompt_lens: Sequence[int], Gs: Se
                                    _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat), Hq, Hkv, d, softmax_scale,
                                    _dtype_code(q), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def sp_attn_probe_atomic_add(buf, rows: int, heads: int, steps: int, n_blocks: int = 512, layout: int = 0, stream=None) -> int:
+    """Enqueue the atomic-add measurement loop; returns the bytes the launch adds."""
+    st = load_library().sp_attn_probe_atomic_add(buf.data_ptr(), rows, heads, steps, n_blocks, layout, _stream_ptr(stream))
+    if st != SP_OK:
+        raise SpAttnError(st, "sp_attn_probe_atomic_add: invalid argument or launch failure")
+    return n_blocks * steps * 32768
 
 
 def set_small_shape_steps(steps: int) -> None:

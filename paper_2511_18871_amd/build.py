@@ -14,6 +14,8 @@ LIB = os.path.join(HERE, "libsp_attn.so")
 SOURCES = ["sp_api.hip", "sp_f32.hip", "sp_fwd.hip", "sp_bwd.hip", "sp_rope.hip", "sp_loss.hip", "sp_probe.hip", "sp_edge.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function", "-fno-honor-nans",
+         # float atomic adds as the hardware instruction (only the measurement probe uses any)
+         "-munsafe-fp-atomics",
          # keep the compiler from forming packed-fp32 VALU ops
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -50,8 +50,46 @@ __global__ __launch_bounds__(512) void mfma_ceiling_kernel(const bf16x8* __restr
     if (blockIdx.x == 0) out[tid] = s;          // keeps the loop alive; 512 floats
 }
 
+// What a backward in ONE pass would cost in memory atomics.  A pass that owns key tiles and produces dK, dV
+// and dQ together has to add a 64 x 128 fp32 partial of dQ into a [T, Hq, 128] accumulator for every
+// (128-key tile, 64-row tile, q head) it visits: 4 bytes per allowed pair and q head.  This kernel does
+// nothing but those additions (no-return global_atomic_add_f32, device scope), from 512-thread workgroups
+// that each add `steps` tiles: layout 0 = each half-wave covers 128 contiguous bytes of a row (what a
+// kernel could arrange through LDS), layout 1 = the lanes scatter as the MFMA accumulator holds dQ^T.
+template <int LAYOUT>
+__global__ __launch_bounds__(512) void atomic_add_probe_kernel(float* __restrict__ buf, int n_row_tiles, int H,
+                                                               int steps, int heads_per_xcd) {
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3;      // XCD the block lands on, slot within it
+    for (int it = 0; it < steps; ++it) {
+        const int head = (x * heads_per_xcd + (j + it) % heads_per_xcd) % H;
+        const int rt = (int)(((unsigned)j * 2654435761u + (unsigned)it * 40503u) % (unsigned)n_row_tiles);
+        float* base = buf + ((size_t)rt * 64 * H + head) * 128;
+        const size_t rs = (size_t)H * 128;
+        const float v = 1.0f + it;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            int row, col;
+            if (LAYOUT == 0) { row = 8 * w + 2 * (e >> 2) + (l >> 5); col = (l & 31) + 32 * (e & 3); }
+            else { row = 32 * (w & 1) + (l & 31); col = 32 * (w >> 1) + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3); }
+            __hip_atomic_fetch_add(base + row * rs + col, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 }  // namespace
 }  // namespace sp
+
+extern "C" sp_status sp_attn_probe_atomic_add(float* buf, int64_t rows, int32_t heads, int32_t steps, int32_t n_blocks,
+                                              int32_t layout, void* stream) {
+    if (!buf || rows < 64 || heads < 1 || steps < 1 || n_blocks < 1 || layout < 0 || layout > 1) return SP_ERR_INVALID_ARG;
+    const int n_row_tiles = (int)(rows / 64);
+    const int hpx = heads >= 8 ? heads / 8 : 1;
+    hipStream_t s = (hipStream_t)stream;
+    if (layout == 0) hipLaunchKernelGGL(sp::atomic_add_probe_kernel<0>, dim3(n_blocks), dim3(512), 0, s, buf, n_row_tiles, heads, steps, hpx);
+    else hipLaunchKernelGGL(sp::atomic_add_probe_kernel<1>, dim3(n_blocks), dim3(512), 0, s, buf, n_row_tiles, heads, steps, hpx);
+    return hipGetLastError() == hipSuccess ? SP_OK : SP_ERR_DEVICE;
+}
 
 extern "C" sp_status sp_attn_mfma_ceiling(int32_t lds_operands, const void* a, const void* b, int32_t iters,
                                           int32_t n_blocks, float* out, void* stream) {
