@@ -45,6 +45,18 @@ constexpr size_t TAG_BYTES = 256;
 inline int* table_of(void* workspace) { return (int*)((char*)workspace + TAG_BYTES); }
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
 
+// Bytes of the schedule region that follows the table: key_lo and row_hi per token, then the tile
+// descriptors (sized by upper bounds on the tile counts, so that it depends on the totals alone).
+struct SchedLayout { size_t key_lo, row_hi, tiles256, tiles128, bytes; };
+SchedLayout sched_layout(int64_t total_tokens, int32_t n_groups) {
+    SchedLayout s{};
+    const size_t per_tok = align256((size_t)total_tokens * 4);
+    const size_t b256 = align256(((size_t)total_tokens / 256 + (size_t)n_groups + 1) * sizeof(sp::TileDesc));
+    const size_t b128 = align256(((size_t)total_tokens / 128 + (size_t)n_groups + 1) * sizeof(sp::TileDesc));
+    s.key_lo = 0; s.row_hi = per_tok; s.tiles256 = 2 * per_tok; s.tiles128 = s.tiles256 + b256; s.bytes = s.tiles128 + b128;
+    return s;
+}
+
 size_t table_words(int32_t n_groups, int64_t total_responses) {
     return (size_t)sp::TAB_HEADER + (size_t)sp::TAB_GROUP_WORDS * n_groups + (size_t)total_responses + n_groups;
 }
@@ -177,7 +189,11 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse; p.d_o = d_o;
     p.o_out = o_out; p.lse_out = lse_out; p.dq = dq; p.dk = dk; p.dv = dv;
     p.tab = table_of(workspace);
-    p.Dbuf = (float*)((char*)workspace + TAG_BYTES + align256(L.words.size() * 4));
+    char* const sched_base = (char*)workspace + TAG_BYTES + align256(L.words.size() * 4);
+    const SchedLayout sl = sched_layout(L.total_tokens, n_groups);
+    p.sched = sp::Schedule{(const sp::TileDesc*)(sched_base + sl.tiles256), (const sp::TileDesc*)(sched_base + sl.tiles128),
+                           (const int*)(sched_base + sl.key_lo), (const int*)(sched_base + sl.row_hi)};
+    p.Dbuf = (float*)(sched_base + sl.bytes);
     p.dkdv_partial = (bwd && dtype == SP_BF16 && sp::dkdv_head_split(L.total_tokens, n_groups, Hq, Hkv))
                          ? (float*)((char*)p.Dbuf + align256((size_t)Hq * (size_t)L.total_tokens * 8)) : nullptr;
     p.n_groups = n_groups; p.total_tokens = L.total_tokens; p.max_group_tokens = L.max_group_tokens;
@@ -195,8 +211,12 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.host_group_tokens = L.group_tokens.data();
     p.host_table = L.words.data();
 
+    p.n_tiles256 = sp::count_tiles(p, 256); p.n_tiles128 = sp::count_tiles(p, 128);
     hipError_t e = keep_tag ? hipSuccess : sp::launch_reserve_tag((uint32_t*)workspace, tag, tag_mode, s);
     if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
+    if (e == hipSuccess && dtype == SP_BF16)
+        e = sp::launch_schedule(p.tab, n_groups, L.total_tokens, p.n_tiles256, p.n_tiles128, (sp::TileDesc*)p.sched.tiles256,
+                                (sp::TileDesc*)p.sched.tiles128, (int*)p.sched.key_lo, (int*)p.sched.row_hi, s);
     if (e == hipSuccess) {
         if (dtype == SP_BF16) e = bwd ? sp::launch_bwd_bf16(p, s) : sp::launch_fwd_bf16(p, s);
         else e = bwd ? sp::launch_bwd_f32(p, s) : sp::launch_fwd_f32(p, s);
@@ -213,7 +233,7 @@ size_t sp_attn_workspace_bytes(int is_bwd, int64_t total_tokens, int32_t n_group
                                int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, sp_dtype dtype) {
     (void)head_dim;
     if (total_tokens < 1 || n_groups < 1 || total_responses < 0 || n_q_heads < 1) return 0;
-    size_t bytes = TAG_BYTES + align256(table_words(n_groups, total_responses) * 4);
+    size_t bytes = TAG_BYTES + align256(table_words(n_groups, total_responses) * 4) + sched_layout(total_tokens, n_groups).bytes;
     if (is_bwd) bytes += align256((size_t)n_q_heads * (size_t)total_tokens * 8);   // D and scaled LSE
     if (is_bwd && dtype == SP_BF16 && n_kv_heads > 0 && n_q_heads % n_kv_heads == 0 &&
         sp::dkdv_head_split(total_tokens, n_groups, n_q_heads, n_kv_heads))       // per-q-head dK, dV partials
@@ -336,8 +356,16 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
     p.Hq = n_q_heads; p.Hkv = n_kv_heads; p.head_dim = head_dim; p.scale = softmax_scale;
     p.host_group_tokens = L.group_tokens.data();
     p.host_table = L.words.data();
+    char* const sched_base = (char*)workspace + TAG_BYTES + align256(L.words.size() * 4);
+    const SchedLayout sl = sched_layout(L.total_tokens, n_groups);
+    p.sched = sp::Schedule{(const sp::TileDesc*)(sched_base + sl.tiles256), (const sp::TileDesc*)(sched_base + sl.tiles128),
+                           (const int*)(sched_base + sl.key_lo), (const int*)(sched_base + sl.row_hi)};
+    p.n_tiles256 = sp::count_tiles(p, 256); p.n_tiles128 = sp::count_tiles(p, 128);
     hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
     if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
+    if (e == hipSuccess && dtype == SP_BF16)
+        e = sp::launch_schedule(p.tab, n_groups, L.total_tokens, p.n_tiles256, p.n_tiles128, (sp::TileDesc*)p.sched.tiles256,
+                                (sp::TileDesc*)p.sched.tiles128, (int*)p.sched.key_lo, (int*)p.sched.row_hi, s);
     if (e == hipSuccess) {
         if (dtype == SP_BF16) {
             p.n_sets = n_sets;

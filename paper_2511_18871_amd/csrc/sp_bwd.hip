@@ -28,6 +28,7 @@ struct BwdArgs {
     const float* lse; float* D; const float* L2;   // L2 = lse * log2(e), written by the rowsum stage
     __bf16* dq; __bf16* dk; __bf16* dv;
     const int* tab;
+    Schedule sched;      // tile descriptors and per-token segment bounds, written by the schedule kernel of the call
     int n_tiles, n_groups, Hq, Hkv;
     float scale, c;      // c = scale * log2(e)
     int resp_only;       // only response rows are computed (dq) / contribute (dk, dv)
@@ -51,10 +52,10 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
 
     int tile, head;
     if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
-    int g, ti;
-    find_tile<BM>(a.tab, a.n_groups, tile, g, ti);
-    if (g < 0) return;
-    const GroupDesc gd = load_group(a.tab, g);
+    const TileDesc td = a.sched.tiles256[tile];     // BM == 256
+    const int ti = td.ti;
+    GroupDesc gd;
+    gd.tok_base = td.tok_base; gd.Lp = td.Lp; gd.Tg = td.Tg; gd.G = 0; gd.roff = nullptr;
     const int Lp = gd.Lp, Tg = gd.Tg;
     const int t0 = ((Tg + BM - 1) / BM - 1 - ti) * BM;   // a group's last tile first: it carries the most work
     const int64_t T_total = a.tab[1];
@@ -69,16 +70,9 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     const int tw0 = t0 + 32 * w;
     const bool wave_valid = tw0 < Tg;
     const int tw1 = min(tw0 + 31, Tg - 1);
-    // segment starts of this lane's row and of the workgroup's first response row, one search
-    int st, b2;
-    {
-        const int first_resp = min(max(t0, Lp), Tg - 1);
-        const int tq[2] = {max(min(t, Tg - 1), Lp), max(first_resp, Lp)};
-        int sq[2], eq[2];
-        seg_bounds<2>(gd, tq, sq, eq);
-        st = (valid && t >= Lp) ? sq[0] : 0;
-        b2 = __builtin_amdgcn_readfirstlane(first_resp < Lp ? 0 : sq[1]);
-    }
+    // first own-segment key of this lane's row and of the workgroup's first response row (0 on the prompt)
+    const int st = valid ? a.sched.key_lo[gd.tok_base + t] : 0;
+    const int b2 = __builtin_amdgcn_readfirstlane(a.sched.key_lo[gd.tok_base + min(max(t0, Lp), Tg - 1)]);
     // lanes 0..31 hold the wave's rows in order: the last valid row's start comes from its lane
     const int st_last = wave_valid ? __builtin_amdgcn_readlane(st, tw1 - tw0) : 0;
 
@@ -334,11 +328,13 @@ __shared__ __attribute__((aligned(1024))) char dkdv_ldsKV[2][128 * 256];       /
 __shared__ __attribute__((aligned(1024))) char dkdv_lds[2][2 * TILE_BYTES];    // [buffer][Q | dO]
 __shared__ __attribute__((aligned(256))) float dkdv_ldsLD[2][2][64];           // [buffer][L2 | D][row]
 
-__device__ __forceinline__ void dkdv_body(const BwdArgs& a, const int g, const int ti, const int kvh, const int hr_only) {
+__device__ __forceinline__ void dkdv_body(const BwdArgs& a, const TileDesc td, const int kvh, const int hr_only) {
+    const int ti = td.ti;
     constexpr int BNK = 128, BQ = 64;
     constexpr int RD = 3;      // LDS operand ring depth (prefetch distance RD - 1 MFMAs)
     const int s0 = ti * BNK;
-    const GroupDesc gd = load_group(a.tab, g);
+    GroupDesc gd;
+    gd.tok_base = td.tok_base; gd.Lp = td.Lp; gd.Tg = td.Tg; gd.G = 0; gd.roff = nullptr;
     const int Lp = gd.Lp, Tg = gd.Tg;
     const int64_t T_total = a.tab[1];
 
@@ -353,15 +349,10 @@ __device__ __forceinline__ void dkdv_body(const BwdArgs& a, const int g, const i
     const bool wave_valid = ws0 < Tg;
     const int ws1 = min(ws0 + 31, Tg - 1);             // wave's last valid key
     const int s1 = min(s0 + BNK, Tg);
-    // segment ends of this lane's key and of the workgroup's last key, found in one search
-    int e_s, row_end;                                  // row_end: rows that see any key of the tile end here
-    {
-        const int tq[2] = {max(min(s, Tg - 1), Lp), max(s1 - 1, Lp)};
-        int sq[2], eq[2];
-        seg_bounds<2>(gd, tq, sq, eq);
-        e_s = !valid ? 0 : (s < Lp ? Tg : eq[0]);
-        row_end = __builtin_amdgcn_readfirstlane(s0 < Lp ? Tg : eq[1]);
-    }
+    // rows [s, e_s) see this lane's key; row_end: where the rows that see any key of the tile end (the
+    // group's end if the tile holds a prompt key, else the end of its last key's response)
+    const int e_s = valid ? a.sched.row_hi[gd.tok_base + s] : 0;
+    const int row_end = __builtin_amdgcn_readfirstlane(s0 < Lp ? Tg : a.sched.row_hi[gd.tok_base + s1 - 1]);
     // smallest / largest row bound e_s over the wave's keys (prompt keys: Tg; response keys: the
     // end of their response, non-decreasing in s); lanes 0..31 hold the wave's keys in order
     const int e_min = !wave_valid ? 0 : (ws1 < Lp ? Tg : __builtin_amdgcn_readlane(e_s, max(ws0, Lp) - ws0));
@@ -689,10 +680,7 @@ __global__ __launch_bounds__(512) void bwd_dkdv_kernel(BwdArgs a) {
         hr_only = head % (a.Hq / a.Hkv);
     } else if (!decode_item(blockIdx.x, a.n_tiles, a.Hkv, a.Hkv, tile, kvh)) return;
     // key tiles in ascending order: the first prompt tile is seen by every row (most work)
-    int g, ti;
-    find_tile<128>(a.tab, a.n_groups, tile, g, ti);
-    if (g < 0) return;
-    dkdv_body(a, g, ti, kvh, hr_only);
+    dkdv_body(a, a.sched.tiles128[tile], kvh, hr_only);
 }
 
 // Second stage of the head-split dkdv pass: dk = scale * sum_hr partial[0][hr], dv = sum_hr
@@ -735,7 +723,7 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v; a.d_o = (const __bf16*)p.d_o;
     a.lse = p.lse; a.D = p.Dbuf; a.L2 = p.Dbuf + (int64_t)p.Hq * p.total_tokens;
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;
-    a.tab = p.tab; a.n_groups = p.n_groups; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
+    a.tab = p.tab; a.sched = p.sched; a.n_groups = p.n_groups; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
     a.resp_only = p.resp_only; a.accumulate = p.accumulate;
     if (p.stages & STAGE_DQ) {
         constexpr int NWQ = 8;

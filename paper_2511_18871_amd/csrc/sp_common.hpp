@@ -128,6 +128,17 @@ __device__ __forceinline__ void find_tile(const int* __restrict__ tab, int n_gro
     idx_out = idx;
 }
 
+// Schedule: what the MFMA kernels' prologues would otherwise look up in the table through chains of
+// dependent loads, written once per call by a small kernel (sp_f32.hip: schedule_kernel).
+//   TileDesc  per work tile (one array for tiles of 256, one for tiles of 128 rows or keys): its group
+//             and index inside the group, and the group's first token, prompt length and token count
+//   key_lo[tok]  first key of its own segment that token tok may attend besides the prompt
+//                (group-local; 0 for a prompt token): the mask is s <= t && (s < Lp || s >= key_lo[t])
+//   row_hi[tok]  one past the last row that sees token tok as a key (group-local): the group's end for
+//                a prompt token, the end of its response otherwise
+struct TileDesc { int g, ti, tok_base, Lp, Tg, pad0, pad1, pad2; };
+struct Schedule { const TileDesc* tiles256; const TileDesc* tiles128; const int* key_lo; const int* row_hi; };
+
 // Map a flat block index to (tile, q head) so that the blocks an XCD receives
 // (blocks are dealt round-robin over the 8 XCDs, each with a private L2) share one
 // kv head, and q heads of the same tile sit next to each other.

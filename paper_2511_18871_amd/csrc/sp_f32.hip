@@ -6,6 +6,7 @@
 // MFMA, no LDS: they exist to cross-check the MFMA path and to serve float32 callers.
 #include "sp_common.hpp"
 #include "sp_launch.hpp"
+#include <type_traits>
 
 namespace sp {
 namespace {
@@ -23,6 +24,38 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 __global__ void upload_table_kernel(TabChunk chunk, int* __restrict__ dst, int offset, int count) {
     for (int i = threadIdx.x; i < count; i += blockDim.x) dst[offset + i] = chunk.w[i];
+}
+
+// One thread per packed token writes its segment bounds, one per work tile its descriptor (see Schedule).
+__global__ __launch_bounds__(256) void schedule_kernel(const int* __restrict__ tab, int n_groups, int64_t T_total,
+                                                       int n256, int n128, TileDesc* __restrict__ tiles256,
+                                                       TileDesc* __restrict__ tiles128, int* __restrict__ key_lo,
+                                                       int* __restrict__ row_hi) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < T_total) {
+        const GroupDesc gd = load_group(tab, find_group_of_token(tab, i));
+        const int t = (int)(i - gd.tok_base);
+        int lo = 0, hi = gd.Tg;
+        if (t >= gd.Lp) {
+            const int tq[1] = {t};
+            int sq[1], eq[1];
+            seg_bounds<1>(gd, tq, sq, eq);
+            lo = sq[0]; hi = eq[0];
+        }
+        key_lo[i] = lo;
+        row_hi[i] = hi;
+    }
+    auto describe = [&](auto bt_tag, int n, TileDesc* out) {
+        constexpr int BT = decltype(bt_tag)::value;
+        if (i >= n) return;
+        int g, ti;
+        find_tile<BT>(tab, n_groups, (int)i, g, ti);
+        if (g < 0) g = n_groups - 1;                   // cannot happen: n is the exact tile count
+        const GroupDesc gd = load_group(tab, g);
+        out[i] = TileDesc{g, ti, gd.tok_base, gd.Lp, gd.Tg, 0, 0, 0};
+    };
+    describe(std::integral_constant<int, 256>{}, n256, tiles256);
+    describe(std::integral_constant<int, 128>{}, n128, tiles128);
 }
 
 // Tag block maintenance, one wave.  See sp_launch.hpp for the modes.  A reserve written for all rows
@@ -321,6 +354,15 @@ __global__ __launch_bounds__(256) void bwd_dkdv_f32_kernel(const float* __restri
 inline int blocks_for_waves(int64_t waves) { return (int)((waves + 3) / 4); }
 
 }  // namespace
+
+hipError_t launch_schedule(const int* tab, int n_groups, int64_t total_tokens, int n256, int n128, TileDesc* tiles256,
+                           TileDesc* tiles128, int* key_lo, int* row_hi, hipStream_t s) {
+    int64_t n = total_tokens;
+    if (n128 > n) n = n128;                            // n128 >= n256
+    hipLaunchKernelGGL(schedule_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, tab, n_groups, total_tokens,
+                       n256, n128, tiles256, tiles128, key_lo, row_hi);
+    return hipGetLastError();
+}
 
 hipError_t launch_reserve_tag(uint32_t* tag_block, const ReserveTag& tag, int mode, hipStream_t s) {
     hipLaunchKernelGGL(reserve_tag_kernel, dim3(1), dim3(64), 0, s, tag_block, tag, mode);

@@ -31,6 +31,7 @@ struct FwdArgs {
     __bf16* o[MAX_SETS]; float* lse[MAX_SETS];
     int blocks_per_set;
     const int* tab;
+    Schedule sched; // tile descriptors and per-token segment bounds, written by the schedule kernel of the call
     int n_tiles, n_groups, Hq, Hkv;
     float c;        // softmax_scale * log2(e)
     int naive;
@@ -56,7 +57,10 @@ struct FwdArgs {
 // per barrier, TWO workgroups per CU: each workgroup's fixed costs (table lookups, first loads,
 // epilogue, the gap before the next dispatch) then overlap with the other's key loop, which is what
 // batches of short groups need, where a workgroup runs only a handful of steps.
-template <int NW>
+// NAIVE = the measurement baseline (every tile at or below the packed diagonal, mask applied element by
+// element): a separate instantiation, so that it shows under its own name in kernel traces and its
+// branches cost the product kernel nothing.
+template <int NW, bool NAIVE>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // two waves per SIMD in either shape
     constexpr int BM = 32 * NW;
     constexpr int NB = NW == 8 ? 4 : 2;            // K buffers = V buffers
@@ -71,10 +75,11 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
     __bf16* const ao = a.o[set]; float* const alse = a.lse[set];
     int tile, head;
     if (!decode_item(blockIdx.x - set * a.blocks_per_set, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
-    int g, ti;
-    find_tile<BM>(a.tab, a.n_groups, tile, g, ti);
-    if (g < 0) return;
-    const GroupDesc gd = load_group(a.tab, g);
+    // the tile's descriptor: one 32-byte load instead of a bisection over the groups and the group's entry
+    const TileDesc td = (BM == 256 ? a.sched.tiles256 : a.sched.tiles128)[tile];
+    const int ti = td.ti;
+    GroupDesc gd;
+    gd.tok_base = td.tok_base; gd.Lp = td.Lp; gd.Tg = td.Tg; gd.G = 0; gd.roff = nullptr;
     const int Lp = gd.Lp, Tg = gd.Tg;
     const int t0 = ((Tg + BM - 1) / BM - 1 - ti) * BM;   // a group's last tile first: it carries the most work
     const int T_total = a.tab[1];
@@ -89,16 +94,9 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
     const int tw0 = t0 + 32 * w;
     const bool wave_valid = tw0 < Tg;
     const int tw1 = min(tw0 + 31, Tg - 1);
-    // segment starts of this lane's row and of the workgroup's first response row, one search
-    int st, b2;
-    {
-        const int first_resp = min(max(t0, Lp), Tg - 1);
-        const int tq[2] = {max(min(t, Tg - 1), Lp), max(first_resp, Lp)};
-        int sq[2], eq[2];
-        seg_bounds<2>(gd, tq, sq, eq);
-        st = (valid && t >= Lp) ? sq[0] : 0;
-        b2 = __builtin_amdgcn_readfirstlane(first_resp < Lp ? 0 : sq[1]);
-    }
+    // first own-segment key of this lane's row and of the workgroup's first response row (0 on the prompt)
+    const int st = valid ? a.sched.key_lo[gd.tok_base + t] : 0;
+    const int b2 = __builtin_amdgcn_readfirstlane(a.sched.key_lo[gd.tok_base + min(max(t0, Lp), Tg - 1)]);
     // lanes 0..31 hold the wave's rows in order: the last valid row's start comes from its lane
     const int st_last = wave_valid ? __builtin_amdgcn_readlane(st, tw1 - tw0) : 0;
 
@@ -114,7 +112,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
 
     const int t1 = min(t0 + BM, Tg);
     int n1, k2b, k2e;
-    if (a.naive) {
+    if (NAIVE) {
         n1 = (t1 + BN - 1) / BN; k2b = k2e = n1;
     } else {
         n1 = (min(Lp, t1) + BN - 1) / BN;
@@ -179,10 +177,10 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
     // true when some (row, key) pair of this wave in tile `it` is masked; tiles past the end
     // of the key range (the pad step of an odd-length loop) are masked entirely
     // the first n_full tiles (whole prompt tiles at or below the wave's first row) never need it
-    const int n_full = (!wave_valid || a.naive) ? 0 : __builtin_amdgcn_readfirstlane(min(min(Lp, tw0 + 1) / BN, n1));
+    const int n_full = (!wave_valid || NAIVE) ? 0 : __builtin_amdgcn_readfirstlane(min(min(Lp, tw0 + 1) / BN, n1));
     auto needs_mask = [&](int it) -> bool {
         if (it < n_full) return false;
-        if (it >= total || !wave_valid || a.naive) return true;
+        if (it >= total || !wave_valid || NAIVE) return true;
         const int s0 = tile_at(it) * BN;
         return !((s0 + BN - 1 <= tw0) && (s0 + BN <= Lp || s0 >= st_last));
     };
@@ -502,7 +500,7 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
         a.v[i] = (const __bf16*)(multi ? p.vs[i] : p.v);
         a.o[i] = (__bf16*)(multi ? p.os[i] : p.o_out); a.lse[i] = multi ? p.lses[i] : p.lse_out;
     }
-    a.tab = p.tab; a.n_groups = p.n_groups;
+    a.tab = p.tab; a.n_groups = p.n_groups; a.sched = p.sched;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.c = p.scale * LOG2E; a.naive = p.naive; a.resp_only = p.resp_only;
     a.o_lo = n_sets == 1 ? (__bf16*)p.o_lo_out : nullptr;
     // Short key loops: the 128-row shape, two workgroups per CU (see fwd_kernel).  The naive baseline keeps
@@ -512,8 +510,9 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
     a.n_tiles = count_tiles(p, bm);
     a.blocks_per_set = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
     if (a.blocks_per_set % 8 != 0) a.blocks_per_set += 8 - a.blocks_per_set % 8;
-    if (small) hipLaunchKernelGGL(fwd_kernel<4>, dim3(a.blocks_per_set * n_sets), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(fwd_kernel<8>, dim3(a.blocks_per_set * n_sets), dim3(512), 0, s, a);
+    if (p.naive) hipLaunchKernelGGL((fwd_kernel<8, true>), dim3(a.blocks_per_set * n_sets), dim3(512), 0, s, a);
+    else if (small) hipLaunchKernelGGL((fwd_kernel<4, false>), dim3(a.blocks_per_set * n_sets), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((fwd_kernel<8, false>), dim3(a.blocks_per_set * n_sets), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 

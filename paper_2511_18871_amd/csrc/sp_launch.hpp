@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "sp_common.hpp"
 
 namespace sp {
 
@@ -31,6 +32,8 @@ struct Problem {
     void* os[MAX_SETS]; float* lses[MAX_SETS];
     void* dq; void* dk; void* dv;                         // backward outputs
     const int* tab;                                       // segment table (device)
+    Schedule sched;                                       // tile descriptors and per-token segment bounds (device)
+    int n_tiles256, n_tiles128;                           // exact tile counts of the packing
     float* Dbuf;                                          // [Hq, T_total] rowsum(dO*O) (device)
     int n_groups;
     int64_t total_tokens;
@@ -72,6 +75,8 @@ hipError_t launch_grpo(const float* logp, const float* old, const float* ref, co
                        float* J, float* loss, const int* tab, int n_resp, int n_nonempty, float eps_low,
                        float eps_high, float beta, hipStream_t s);
 hipError_t launch_reserve_tag(uint32_t* tag_block, const ReserveTag& tag, int mode, hipStream_t s);
+hipError_t launch_schedule(const int* tab, int n_groups, int64_t total_tokens, int n256, int n128, TileDesc* tiles256,
+                           TileDesc* tiles128, int* key_lo, int* row_hi, hipStream_t s);
 hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s);
 
 // Packings whose 256-row workgroups would run fewer 64-key steps than this on average take the kernels'
