@@ -14,8 +14,8 @@ What it computes (paper Section 4.3):
   up to and including itself; it never sees another response.  The prompt is
   causal.  The mask is materialised as an explicit T x T boolean matrix.
 * Masked softmax attention with that mask, and its exact gradient.  The paper
-  states the result equals per-sample training "with no approximation", so the
-  oracle is the textbook definition written out, in float64:
+  states that the result equals per-sample training exactly (it is not an
+  approximation), so the oracle is the textbook definition written out, in float64:
 
       S = scale * Q K^T          LSE_t = log sum_{s allowed} exp(S_ts)
       P = exp(S - LSE) on allowed pairs, 0 elsewhere          O = P V
