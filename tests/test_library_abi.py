@@ -201,3 +201,45 @@ def test_segment_table_errors(lib):
     assert b"empty" in lib.sp_attn_last_error()
     assert lib.sp_attn_segment_table(0, i32([]), i32([]), i32([]), None, 0, ctypes.byref(n)) == B.SP_ERR_INVALID_ARG
     assert lib.sp_attn_segment_table(1, i32([10]), i32([0]), None, None, 0, None) == B.SP_ERR_INVALID_ARG
+
+
+def test_reserve_and_workspace_sizes(lib):
+    """The forward-to-backward reserve: size formula, zero for fp32 and for arguments no call accepts; a
+    workspace with room for it is the backward's size plus the reserve."""
+    T, Hq, d = 1000, 8, 128
+    assert B.reserve_bytes(T, Hq, d, B.SP_BF16) == (T * Hq * d * 2 + 255) // 256 * 256
+    assert B.reserve_bytes(T, Hq, d, B.SP_F32) == 0
+    assert B.reserve_bytes(0, Hq, d, B.SP_BF16) == 0 and B.reserve_bytes(T, 0, d, B.SP_BF16) == 0
+    fwd = B.workspace_bytes(False, T, 3, 9, Hq, 2, d, B.SP_BF16)
+    bwd = B.workspace_bytes(True, T, 3, 9, Hq, 2, d, B.SP_BF16)
+    # tag block, table, schedule (two ints per token and a descriptor per tile of 256 and of 128)
+    assert fwd >= 256 + (4 + 8 * 3 + 9 + 3) * 4 + 8 * T + 32 * (T // 256 + T // 128)
+    assert bwd > fwd and fwd % 256 == 0 and bwd % 256 == 0
+    # more groups or more responses never need less
+    assert B.workspace_bytes(True, T, 30, 90, Hq, 2, d, B.SP_BF16) >= bwd
+
+
+def test_measurement_aids_and_knob_reject_bad_arguments(lib):
+    P = 0x1000
+    assert lib.sp_attn_mfma_ceiling(3, P, P, 10, 256, P, None) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_mfma_ceiling(0, None, P, 10, 256, P, None) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_mfma_ceiling(0, 0x1004, P, 10, 256, P, None) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_mfma_ceiling(0, P, P, 0, 256, P, None) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_probe_atomic_add(None, 64, 8, 1, 1, 0, None) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_probe_atomic_add(P, 63, 8, 1, 1, 0, None) == B.SP_ERR_INVALID_ARG
+    assert lib.sp_attn_probe_atomic_add(P, 64, 8, 1, 1, 2, None) == B.SP_ERR_INVALID_ARG
+    B.set_small_shape_steps(0)
+    B.set_small_shape_steps(-1)            # back to the default; no return value, must not raise
+
+
+def test_rope_qk_argument_checks(lib):
+    i32 = lambda xs: (ctypes.c_int32 * max(1, len(xs)))(*xs)
+    P = 0x1000
+    f = lambda **kw: lib.sp_attn_rope_qk(kw.get("q", P), P, kw.get("Hq", 4), kw.get("k", P), kw.get("ko", P), 2, 0, 1,
+                                         i32([10]), i32([1]), i32([5]), kw.get("d", 128), kw.get("base", 1e4), B.SP_BF16,
+                                         kw.get("ws", P), 1 << 20, None)
+    assert f(q=None) == B.SP_ERR_INVALID_ARG and f(k=None) == B.SP_ERR_INVALID_ARG and f(ko=None) == B.SP_ERR_INVALID_ARG
+    assert f(k=0x1008) == B.SP_ERR_INVALID_ARG
+    assert f(Hq=0) == B.SP_ERR_INVALID_ARG and f(base=1.0) == B.SP_ERR_INVALID_ARG
+    assert f(d=96) == B.SP_ERR_UNSUPPORTED
+    assert f(ws=None) == B.SP_ERR_WORKSPACE
