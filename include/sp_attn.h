@@ -156,6 +156,10 @@ sp_status sp_attn_bwd_batched(const void* q, const void* k, const void* v,
  * accurate one when no reserve is used, and the only one whose results are bitwise repeatable from
  * run to run.  To overlap the two gradient passes, give each its own workspace and run ROWSUM on
  * both.  Output pointers of stages that are not requested may be NULL.
+ * A bf16 call that holds both ROWSUM and DQ (and is not in response-rows mode) runs no separate
+ * rowsum kernel: the dq pass, which loads every row of d_o anyway, forms D and lse * log2(e) in its
+ * prologue, with the same operations in the same order, so that the results equal those of the
+ * stages enqueued one by one bit for bit.
  * sp_attn_bwd_batched(...) is this call with SP_BWD_STAGE_ALL. */
 #define SP_BWD_STAGE_ROWSUM 1u
 #define SP_BWD_STAGE_DKDV   2u

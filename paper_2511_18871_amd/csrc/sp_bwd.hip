@@ -25,7 +25,11 @@ constexpr int TILE_BYTES = 64 * 256;   // 64 rows x 128 bf16
 
 struct BwdArgs {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* d_o;
-    const float* lse; float* D; const float* L2;   // L2 = lse * log2(e), written by the rowsum stage
+    const float* lse; float* D; float* L2;         // L2 = lse * log2(e), written by the rowsum stage (or the dq pass, below)
+    // dq pass with the rowsum stage folded in: D = rowsum(dO * (o + residual)) is formed in the prologue from
+    // the dO rows the pass loads anyway, and the D / L2 planes are written for the dkdv pass
+    int fused_rowsum;
+    const __bf16* o; const __bf16* o_lo; const uint32_t* lo_flag;
     __bf16* dq; __bf16* dk; __bf16* dv;
     const int* tab;
     Schedule sched;      // tile descriptors and per-token segment bounds, written by the schedule kernel of the call
@@ -88,7 +92,39 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
             qreg[ks] = *reinterpret_cast<const bf16x8*>(a.q + row + 16 * ks);
             goreg[ks] = *reinterpret_cast<const bf16x8*>(a.d_o + row + 16 * ks);
         }
-        if (valid) {
+        if (a.fused_rowsum) {
+            // The arithmetic of rowsum_bf16_kernel, operation for operation, so that a backward in one call
+            // and a staged one agree bit for bit: that kernel gives a row to 16 lanes of 8 elements each
+            // (lane `sub` = elements 8 sub .. 8 sub + 7, summed in order by fma) and adds the lanes in an
+            // xor-shuffle tree (8, 4, 2, 1).  This lane holds the chunks sub = 2 ks + hh, so the first three
+            // levels are sums inside the lane and the last one is the exchange with the row's other lane.
+            const bool use_lo = a.o_lo != nullptr &&
+                                (a.lo_flag == nullptr || __builtin_amdgcn_readfirstlane((int)*a.lo_flag) != 0);
+            float ch[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 ov = *reinterpret_cast<const bf16x8*>(a.o + row + 16 * ks);
+                float acc1 = 0.f;
+                if (use_lo) {
+                    const bf16x8 lv = *reinterpret_cast<const bf16x8*>(a.o_lo + row + 16 * ks);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc1 = __builtin_fmaf((float)goreg[ks][e], (float)ov[e] + (float)lv[e], acc1);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc1 = __builtin_fmaf((float)goreg[ks][e], (float)ov[e], acc1);
+                }
+                ch[ks] = acc1;
+            }
+            const float x0 = ch[0] + ch[4], x1 = ch[1] + ch[5], x2 = ch[2] + ch[6], x3 = ch[3] + ch[7];
+            const float y0 = x0 + x2, y1 = x1 + x3;
+            Dq = pair_sum(y0 + y1);
+            if (valid) {
+                Lq = a.lse[(int64_t)head * T_total + gd.tok_base + t] * LOG2E;
+                if (hh == 0) a.L2[(int64_t)head * T_total + gd.tok_base + t] = Lq;
+            } else {
+                Dq = 0.f;
+            }
+        } else if (valid) {
             Lq = a.L2[(int64_t)head * T_total + gd.tok_base + t];
             Dq = a.D[(int64_t)head * T_total + gd.tok_base + t];
         }
@@ -715,11 +751,17 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restric
 
 hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     hipError_t e = hipSuccess;
-    if (p.stages & STAGE_ROWSUM) {
+    // A call that runs both the rowsum and the dq stage folds the first into the second (the dq pass has
+    // the dO rows in registers anyway): one pass over o and dO less.  Not in response-rows mode, where the
+    // dq pass skips the prompt's tiles and the dkdv pass still needs finite planes for every row it loads,
+    // and not for head counts that the layout of rowsum_bf16_kernel (whose arithmetic the fold repeats) does not take.
+    const bool fused = (p.stages & STAGE_ROWSUM) && (p.stages & STAGE_DQ) && !p.resp_only && rowsum_fast_path(p);
+    if ((p.stages & STAGE_ROWSUM) && !fused) {
         e = launch_rowsum(p, false, s);
         if (e != hipSuccess) return e;
     }
     BwdArgs a{};
+    a.fused_rowsum = fused; a.o = (const __bf16*)p.o; a.o_lo = (const __bf16*)p.o_lo; a.lo_flag = p.o_lo_flag;
     a.q = (const __bf16*)p.q; a.k = (const __bf16*)p.k; a.v = (const __bf16*)p.v; a.d_o = (const __bf16*)p.d_o;
     a.lse = p.lse; a.D = p.Dbuf; a.L2 = p.Dbuf + (int64_t)p.Hq * p.total_tokens;
     a.dq = (__bf16*)p.dq; a.dk = (__bf16*)p.dk; a.dv = (__bf16*)p.dv;

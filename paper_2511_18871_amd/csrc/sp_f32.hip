@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ d_o, 
 // that each head's RS_TOK tokens leave as one contiguous store into the [Hq, T] planes.  In
 // response-rows mode the prompt rows are still read (the buffers are whole) but their values are
 // discarded by a select, never used in arithmetic that reaches the output.
-constexpr int RS_TOK = 16;
+constexpr int RS_TOK = 16;      // rowsum_fast_path() in sp_launch.hpp assumes this value
 template <bool HAS_LO>
 __global__ __launch_bounds__(256) void rowsum_bf16_kernel(const __bf16* __restrict__ d_o, const __bf16* __restrict__ o,
                                                           const float* __restrict__ lse, float* __restrict__ D,
@@ -387,7 +387,7 @@ hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {
     if (f32)
         hipLaunchKernelGGL(rowsum_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)p.d_o,
                            (const float*)p.o, p.lse, p.Dbuf, p.total_tokens, p.Hq, p.head_dim, p.tab, p.resp_only, (const float*)nullptr);
-    else if (p.head_dim == 128 && (size_t)p.Hq * RS_TOK * sizeof(float) <= 32768) {
+    else if (rowsum_fast_path(p)) {
         const dim3 g((unsigned)((p.total_tokens + RS_TOK - 1) / RS_TOK));
         const size_t lds = (size_t)p.Hq * RS_TOK * sizeof(float);
         if (p.o_lo)

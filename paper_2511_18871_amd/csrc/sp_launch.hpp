@@ -83,6 +83,9 @@ hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_
 // 128-row shape (two workgroups per CU).  SP_ATTN_SMALL_STEPS overrides the default, for measurements.
 int small_shape_steps();
 
+// Packings that the bandwidth-shaped bf16 rowsum kernel takes (its per-head sums of 16 tokens fit its LDS)
+inline bool rowsum_fast_path(const Problem& p) { return p.head_dim == 128 && (size_t)p.Hq * 16 * sizeof(float) <= 32768; }
+
 inline int count_tiles(const Problem& p, int bm) {
     int n = 0;
     for (int g = 0; g < p.n_groups; ++g) n += (p.host_group_tokens[g] + bm - 1) / bm;
