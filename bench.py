@@ -280,9 +280,10 @@ def main():
         # the attention kernels against the ceiling of their own operand mix on random data
         out["fwd"]["pct_of_measured_ceiling"] = round(100.0 * fwd_tf / ceil["random_lds1"], 1)
         if do_bwd:
-            # executed rates: the dq pass runs 6*d and the dkdv pass 8*d FLOPs per allowed pair and q head
+            # executed rates: the dq pass (timed with the rowsum folded in and the edge kernel) runs 6*d and the dkdv pass 8*d FLOPs
+            # per allowed pair and q head
             pairs_hq = fwd_flops / (4.0 * d)
-            dq_exec = 6.0 * d * pairs_hq / (stage_ms["bwd_dq"] * 1e-3) / 1e12
+            dq_exec = 6.0 * d * pairs_hq / (stage_ms["bwd_rowsum_dq"] * 1e-3) / 1e12
             dkdv_exec = 8.0 * d * pairs_hq / (stage_ms["bwd_dkdv"] * 1e-3) / 1e12
             out["bwd"]["dq_executed_tflops"] = round(dq_exec, 1)
             out["bwd"]["dkdv_executed_tflops"] = round(dkdv_exec, 1)
@@ -408,7 +409,7 @@ def main():
                                    "one_pass_dq_ms_at_best_rate": round(need / (max(res.values()) * 1e9) * 1e3, 2),
                                    "note": "fp32 atomic adds a one-pass backward would issue for dQ (4 bytes per allowed "
                                            "pair and q head) against this box's measured rate; the dq pass takes "
-                                           f"{stage_ms.get('bwd_dq', 0.0):.2f} ms"}
+                                           f"{stage_ms.get('bwd_rowsum_dq', 0.0):.2f} ms"}
         del acc
 
     if args.calib_copy:

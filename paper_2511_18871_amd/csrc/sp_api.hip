@@ -212,11 +212,9 @@ sp_status run(bool bwd, const void* q, const void* k, const void* v, const void*
     p.host_table = L.words.data();
 
     p.n_tiles256 = sp::count_tiles(p, 256); p.n_tiles128 = sp::count_tiles(p, 128);
-    hipError_t e = keep_tag ? hipSuccess : sp::launch_reserve_tag((uint32_t*)workspace, tag, tag_mode, s);
-    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
-    if (e == hipSuccess && dtype == SP_BF16)
-        e = sp::launch_schedule(p.tab, n_groups, L.total_tokens, p.n_tiles256, p.n_tiles128, (sp::TileDesc*)p.sched.tiles256,
-                                (sp::TileDesc*)p.sched.tiles128, (int*)p.sched.key_lo, (int*)p.sched.row_hi, s);
+    hipError_t e = sp::launch_prepare(L.words.data(), (int)L.words.size(), table_of(workspace), (uint32_t*)workspace, tag,
+                                      keep_tag ? sp::TAG_KEEP : tag_mode, dtype == SP_BF16, n_groups, L.total_tokens,
+                                      p.n_tiles256, p.n_tiles128, p.sched, s);
     if (e == hipSuccess) {
         if (dtype == SP_BF16) e = bwd ? sp::launch_bwd_bf16(p, s) : sp::launch_fwd_bf16(p, s);
         else e = bwd ? sp::launch_bwd_f32(p, s) : sp::launch_fwd_f32(p, s);
@@ -361,11 +359,9 @@ sp_status sp_attn_fwd_multi(int32_t n_sets, const void* const* q, const void* co
     p.sched = sp::Schedule{(const sp::TileDesc*)(sched_base + sl.tiles256), (const sp::TileDesc*)(sched_base + sl.tiles128),
                            (const int*)(sched_base + sl.key_lo), (const int*)(sched_base + sl.row_hi)};
     p.n_tiles256 = sp::count_tiles(p, 256); p.n_tiles128 = sp::count_tiles(p, 128);
-    hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
-    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
-    if (e == hipSuccess && dtype == SP_BF16)
-        e = sp::launch_schedule(p.tab, n_groups, L.total_tokens, p.n_tiles256, p.n_tiles128, (sp::TileDesc*)p.sched.tiles256,
-                                (sp::TileDesc*)p.sched.tiles128, (int*)p.sched.key_lo, (int*)p.sched.row_hi, s);
+    hipError_t e = sp::launch_prepare(L.words.data(), (int)L.words.size(), table_of(workspace), (uint32_t*)workspace,
+                                      sp::ReserveTag{}, sp::TAG_CLEAR, dtype == SP_BF16, n_groups, L.total_tokens,
+                                      p.n_tiles256, p.n_tiles128, p.sched, s);
     if (e == hipSuccess) {
         if (dtype == SP_BF16) {
             p.n_sets = n_sets;
@@ -405,8 +401,8 @@ sp_status rope_call(const void* x, void* y, int32_t H, const void* x2, void* y2,
         return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
                     workspace_bytes, need);
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
-    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
+    hipError_t e = sp::launch_prepare(L.words.data(), (int)L.words.size(), table_of(workspace), (uint32_t*)workspace,
+                                      sp::ReserveTag{}, sp::TAG_CLEAR, false, n_groups, L.total_tokens, 0, 0, sp::Schedule{}, s);
     if (e == hipSuccess)
         e = sp::launch_rope(x, y, H, x2, y2, H2, table_of(workspace), L.total_tokens, head_dim, rope_base, inverse != 0,
                             dtype == SP_F32, s);
@@ -448,8 +444,8 @@ sp_status loss_setup(int32_t n_groups, const int32_t* prompt_lens, const int32_t
         return fail(SP_ERR_WORKSPACE, "workspace %p of %zu bytes; need %zu bytes, 16-byte aligned", workspace,
                     workspace_bytes, need);
     *scratch = (float*)((char*)workspace + TAG_BYTES + align256(L.words.size() * 4));
-    hipError_t e = sp::launch_reserve_tag((uint32_t*)workspace, sp::ReserveTag{}, sp::TAG_CLEAR, s);
-    if (e == hipSuccess) e = sp::launch_upload_table(L.words.data(), (int)L.words.size(), table_of(workspace), s);
+    hipError_t e = sp::launch_prepare(L.words.data(), (int)L.words.size(), table_of(workspace), (uint32_t*)workspace,
+                                      sp::ReserveTag{}, sp::TAG_CLEAR, false, n_groups, L.total_tokens, 0, 0, sp::Schedule{}, s);
     if (e != hipSuccess) return fail(SP_ERR_DEVICE, "HIP launch failed: %s", hipGetErrorString(e));
     return SP_OK;
 }

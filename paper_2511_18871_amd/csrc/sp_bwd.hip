@@ -513,37 +513,56 @@ __device__ __forceinline__ void dkdv_body(const BwdArgs& a, const TileDesc td, c
         const int buf = it & 1;
         wait_vm0();
         __syncthreads();
-        if (it + 1 < n_steps) issue_tile(qt_n, hr_n, buf ^ 1);
         const char* ldsQ = dkdv_lds[buf];
         const char* ldsG = dkdv_lds[buf] + TILE_BYTES;
         const float* ldsL = dkdv_ldsLD[buf][0];
         const float* ldsD = dkdv_ldsLD[buf][1];
         const int r0 = qt * BQ + 32 * qh;              // this wave's 32 rows
+        const int qt_n_issue = qt_n, hr_n_issue = hr_n;
         qt = qt_n; hr = hr_n;
         if (++hr_n == rep) { hr_n = 0; --qt_n; }
         // no row of this wave's half sees any key of this wave
-        const bool skip = !wave_valid || r0 + 31 < max(ws0, row_lo) || r0 >= e_max;
-        if (skip) continue;
-        if (LO && !(r0 < min(Lp, EDGE_LEN) || (Lp < EDGE_LEN && r0 + 31 >= Lp))) continue;   // no short row here
+        const bool skip = !wave_valid || r0 + 31 < max(ws0, row_lo) || r0 >= e_max ||
+                          (LO && !(r0 < min(Lp, EDGE_LEN) || (Lp < EDGE_LEN && r0 + 31 >= Lp)));   // or: no short row here
 
+        // The LDS operands of the step's 32 MFMAs pass through one pair of rings, read RD - 1 MFMAs ahead
+        // without a break between the four products (a product that primed rings of its own would start with
+        // an exposed LDS round trip).  Slice i: 0..7 S = Q K^T, 8..15 dP = dO V^T, 16..23 and 24..31 the dV / dK
+        // updates for the first and the last 16 rows of the block (A operand only: P and dS are in registers).
+        auto ldt = [&](int mm, int i, int part) {       // dV for even i, dK for odd i; db = i / 2
+            const int col4 = 32 * (i >> 1) + 16 * c16 + 4 * (j & 3);
+            const int row4 = 32 * qh + 16 * mm + 4 * hh + (j >> 2);
+            return lds_read_tr4((i & 1) ? ldsQ : ldsG, row4 + 8 * part, col4);
+        };
+        auto fetchA = [&](int i) -> bf16x8 {
+            if (i < 8) return lds_read_row8(ldsQ, 32 * qh + c, 2 * i + hh);
+            if (i < 16) return lds_read_row8(ldsG, 32 * qh + c, 2 * (i - 8) + hh);
+            return cat4(ldt((i - 16) >> 3, i & 7, 0), ldt((i - 16) >> 3, i & 7, 1));
+        };
+        auto fetchB = [&](int i) -> bf16x8 {
+            return lds_read_row8(i < 8 ? ldsK : ldsV, 32 * kb + c, 2 * (i & 7) + hh);
+        };
+        bf16x8 ra[RD], rb[RD];
+        auto advance = [&](int i) {                      // fetch the operands of slice i + RD - 1
+            const int n = i + RD - 1;
+            if (n < 32) ra[n % RD] = fetchA(n);
+            if (n < 16) rb[n % RD] = fetchB(n);
+        };
+        // the first operands are fetched ahead of the issue of the next tile's copies, which every wave takes
+        // part in whether it has work in this step or not
+        if (!skip) {
+#pragma unroll
+            for (int i = 0; i < RD - 1; ++i) { ra[i] = fetchA(i); rb[i] = fetchB(i); }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (it + 1 < n_steps) issue_tile(qt_n_issue, hr_n_issue, buf ^ 1);
+        if (skip) continue;
         f32x16 sacc, pacc;
-        {   // S = Q K^T
-            bf16x8 ra[RD], rb[RD];
 #pragma unroll
-            for (int i = 0; i < RD - 1; ++i) {
-                ra[i] = lds_read_row8(ldsQ, 32 * qh + c, 2 * i + hh);
-                rb[i] = lds_read_row8(ldsK, 32 * kb + c, 2 * i + hh);
-            }
+        for (int i = 0; i < 8; ++i) {       // S = Q K^T
+            advance(i);
+            sacc = mfma32(ra[i % RD], rb[i % RD], i == 0 ? zero16 : sacc);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (i + RD - 1 < 8) {
-                    ra[(i + RD - 1) % RD] = lds_read_row8(ldsQ, 32 * qh + c, 2 * (i + RD - 1) + hh);
-                    rb[(i + RD - 1) % RD] = lds_read_row8(ldsK, 32 * kb + c, 2 * (i + RD - 1) + hh);
-                }
-                sacc = mfma32(ra[i % RD], rb[i % RD], i == 0 ? zero16 : sacc);
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
         // every row of the half sees every key of the wave
         const bool full = r0 >= max(ws1, row_lo) && ws0 + 31 < Tg && r0 + 32 <= e_min;
@@ -557,12 +576,6 @@ __device__ __forceinline__ void dkdv_body(const BwdArgs& a, const TileDesc td, c
         __builtin_amdgcn_sched_barrier(0);
         float Lr[16], Dr[16];
         {   // dP = dO V^T, with the exponentials of rows 0..7 of the block
-            bf16x8 ra[RD], rb[RD];
-#pragma unroll
-            for (int i = 0; i < RD - 1; ++i) {
-                ra[i] = lds_read_row8(ldsG, 32 * qh + c, 2 * i + hh);
-                rb[i] = lds_read_row8(ldsV, 32 * kb + c, 2 * i + hh);
-            }
 #pragma unroll
             for (int gq = 0; gq < 2; ++gq) {
                 const f32x4 L4 = *reinterpret_cast<const f32x4*>(&ldsL[32 * qh + 8 * gq + 4 * hh]);
@@ -572,17 +585,14 @@ __device__ __forceinline__ void dkdv_body(const BwdArgs& a, const TileDesc td, c
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                if (i + RD - 1 < 8) {
-                    ra[(i + RD - 1) % RD] = lds_read_row8(ldsG, 32 * qh + c, 2 * (i + RD - 1) + hh);
-                    rb[(i + RD - 1) % RD] = lds_read_row8(ldsV, 32 * kb + c, 2 * (i + RD - 1) + hh);
-                }
+                advance(8 + i);
                 if (i == 2 || i == 3) {         // D of rows 0..7, L of rows 8..15
                     const f32x4 D4 = *reinterpret_cast<const f32x4*>(&ldsD[32 * qh + 8 * (i - 2) + 4 * hh]);
                     const f32x4 L4 = *reinterpret_cast<const f32x4*>(&ldsL[32 * qh + 8 * i + 4 * hh]);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { Dr[4 * (i - 2) + e] = D4[e]; Lr[4 * i + e] = L4[e]; }
                 }
-                pacc = mfma32(ra[i % RD], rb[i % RD], i == 0 ? zero16 : pacc);
+                pacc = mfma32(ra[(8 + i) % RD], rb[(8 + i) % RD], i == 0 ? zero16 : pacc);
                 sacc[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], cs, -Lr[i]));      // P
                 asm volatile("" : "+v"(sacc[i]));
                 __builtin_amdgcn_sched_barrier(0);
@@ -594,18 +604,10 @@ __device__ __forceinline__ void dkdv_body(const BwdArgs& a, const TileDesc td, c
 #pragma unroll
         for (int q = 0; q < 4; ++q) { pp[q] = pack2(sacc[2 * q], sacc[2 * q + 1]); dd[q] = pack2(pacc[2 * q], pacc[2 * q + 1]); }
         __builtin_amdgcn_sched_barrier(0);
-        // dV^T += dO^T P, dK^T += Q^T dS.  MFMA i of a half: db = i / 2, dV for even i, dK for odd i.
-        auto ldt = [&](int mm, int i, int part) {
-            const int col4 = 32 * (i >> 1) + 16 * c16 + 4 * (j & 3);
-            const int row4 = 32 * qh + 16 * mm + 4 * hh + (j >> 2);
-            return lds_read_tr4((i & 1) ? ldsQ : ldsG, row4 + 8 * part, col4);
-        };
+        // dV^T += dO^T P, dK^T += Q^T dS
         {   // first 16 rows of the block (mm = 0), with the exponentials and dS of rows 8..15
             const bf16x8 p8 = __builtin_bit_cast(bf16x8, u32x4{pp[0], pp[1], pp[2], pp[3]});
             const bf16x8 d8 = __builtin_bit_cast(bf16x8, u32x4{dd[0], dd[1], dd[2], dd[3]});
-            s16x4 ring[RD][2];
-#pragma unroll
-            for (int i = 0; i < RD - 1; ++i) { ring[i][0] = ldt(0, i, 0); ring[i][1] = ldt(0, i, 1); }
 #pragma unroll
             for (int gq = 2; gq < 4; ++gq) {
                 const f32x4 D4 = *reinterpret_cast<const f32x4*>(&ldsD[32 * qh + 8 * gq + 4 * hh]);
@@ -616,8 +618,8 @@ __device__ __forceinline__ void dkdv_body(const BwdArgs& a, const TileDesc td, c
             float tprev = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                if (i + RD - 1 < 8) { ring[(i + RD - 1) % RD][0] = ldt(0, i + RD - 1, 0); ring[(i + RD - 1) % RD][1] = ldt(0, i + RD - 1, 1); }
-                const bf16x8 A = cat4(ring[i % RD][0], ring[i % RD][1]);
+                advance(16 + i);
+                const bf16x8 A = ra[(16 + i) % RD];
                 if (i & 1) dkacc[i >> 1] = mfma32(A, d8, dkacc[i >> 1]);
                 else dvacc[i >> 1] = mfma32(A, p8, dvacc[i >> 1]);
                 float tcur = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[8 + i], cs, -Lr[8 + i]));
@@ -639,14 +641,10 @@ __device__ __forceinline__ void dkdv_body(const BwdArgs& a, const TileDesc td, c
         {   // last 16 rows of the block (mm = 1)
             const bf16x8 p8 = __builtin_bit_cast(bf16x8, u32x4{pp[4], pp[5], pp[6], pp[7]});
             const bf16x8 d8 = __builtin_bit_cast(bf16x8, u32x4{dd[4], dd[5], dd[6], dd[7]});
-            s16x4 ring[RD][2];
-#pragma unroll
-            for (int i = 0; i < RD - 1; ++i) { ring[i][0] = ldt(1, i, 0); ring[i][1] = ldt(1, i, 1); }
-            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                if (i + RD - 1 < 8) { ring[(i + RD - 1) % RD][0] = ldt(1, i + RD - 1, 0); ring[(i + RD - 1) % RD][1] = ldt(1, i + RD - 1, 1); }
-                const bf16x8 A = cat4(ring[i % RD][0], ring[i % RD][1]);
+                advance(24 + i);
+                const bf16x8 A = ra[(24 + i) % RD];
                 if (i & 1) dkacc[i >> 1] = mfma32(A, d8, dkacc[i >> 1]);
                 else dvacc[i >> 1] = mfma32(A, p8, dvacc[i >> 1]);
                 __builtin_amdgcn_sched_barrier(0);

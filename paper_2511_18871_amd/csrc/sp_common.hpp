@@ -34,6 +34,8 @@ constexpr int TAB_TILES128 = 6;        // 128-key tiles before this group
 constexpr int TAB_CHUNK_WORDS = 960;   // words carried by one upload launch (kernarg limit 4 KB)
 
 struct TabChunk { int32_t w[TAB_CHUNK_WORDS]; };
+constexpr int PREP_WORDS = 896;        // largest table that travels beside the other arguments of the one-launch preparation
+struct PrepChunk { int32_t w[PREP_WORDS]; };
 
 struct GroupDesc {
     int tok_base;       // first packed token of the group

@@ -27,10 +27,9 @@ __global__ void upload_table_kernel(TabChunk chunk, int* __restrict__ dst, int o
 }
 
 // One thread per packed token writes its segment bounds, one per work tile its descriptor (see Schedule).
-__global__ __launch_bounds__(256) void schedule_kernel(const int* __restrict__ tab, int n_groups, int64_t T_total,
-                                                       int n256, int n128, TileDesc* __restrict__ tiles256,
-                                                       TileDesc* __restrict__ tiles128, int* __restrict__ key_lo,
-                                                       int* __restrict__ row_hi) {
+__device__ __forceinline__ void schedule_body(const int* __restrict__ tab, int n_groups, int64_t T_total, int n256,
+                                              int n128, TileDesc* __restrict__ tiles256, TileDesc* __restrict__ tiles128,
+                                              int* __restrict__ key_lo, int* __restrict__ row_hi) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < T_total) {
         const GroupDesc gd = load_group(tab, find_group_of_token(tab, i));
@@ -58,10 +57,17 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int* __restrict__ t
     describe(std::integral_constant<int, 128>{}, n128, tiles128);
 }
 
+__global__ __launch_bounds__(256) void schedule_kernel(const int* __restrict__ tab, int n_groups, int64_t T_total,
+                                                       int n256, int n128, TileDesc* __restrict__ tiles256,
+                                                       TileDesc* __restrict__ tiles128, int* __restrict__ key_lo,
+                                                       int* __restrict__ row_hi) {
+    schedule_body(tab, n_groups, T_total, n256, n128, tiles256, tiles128, key_lo, row_hi);
+}
+
 // Tag block maintenance, one wave.  See sp_launch.hpp for the modes.  A reserve written for all rows
 // (word 10 = 0) also serves a backward over response rows only (want word 10 = 1), not the reverse.
-__global__ __launch_bounds__(64) void reserve_tag_kernel(uint32_t* __restrict__ blk, ReserveTag want, int mode) {
-    const int i = threadIdx.x;
+__device__ __forceinline__ void reserve_tag_body(uint32_t* __restrict__ blk, const ReserveTag& want, int mode) {
+    const int i = threadIdx.x;                  // one whole wave: lanes 0..63
     if (mode == TAG_CLEAR) { blk[i] = 0u; return; }
     if (mode == TAG_WRITE) { blk[i] = i < TAG_WORDS ? want.w[i] : 0u; return; }
     const uint32_t have = blk[i];
@@ -70,6 +76,32 @@ __global__ __launch_bounds__(64) void reserve_tag_kernel(uint32_t* __restrict__ 
     const bool ok = __builtin_amdgcn_ballot_w64(!same) == 0;
     if (i < TAG_WORDS && !ok) blk[i] = 0u;
     if (i == TAG_FLAG_WORD) blk[i] = ok ? 1u : 0u;
+}
+
+__global__ __launch_bounds__(64) void reserve_tag_kernel(uint32_t* __restrict__ blk, ReserveTag want, int mode) {
+    reserve_tag_body(blk, want, mode);
+}
+
+// Everything a call does ahead of its attention kernels, in one launch, for segment tables that fit one
+// kernel-argument block: block 0 stores the table into the workspace and (first wave) maintains the tag
+// block; every block works out its part of the schedule from a copy of the table in its own LDS, since the
+// copy in memory is only complete when the kernel has ended.  Small problems, whose attention kernels run
+// for tens of microseconds, otherwise spend a fifth of a call in three tiny launches and the gaps between them.
+__global__ __launch_bounds__(256) void prepare_kernel(PrepChunk chunk, int n_words, int* __restrict__ dev_tab,
+                                                      uint32_t* __restrict__ tag_blk, ReserveTag want, int tag_mode,
+                                                      int with_schedule, int n_groups, int64_t T_total, int n256,
+                                                      int n128, TileDesc* __restrict__ tiles256,
+                                                      TileDesc* __restrict__ tiles128, int* __restrict__ key_lo,
+                                                      int* __restrict__ row_hi) {
+    __shared__ int tab_s[PREP_WORDS];
+    for (int i = threadIdx.x; i < n_words; i += 256) {
+        const int x = chunk.w[i];
+        tab_s[i] = x;
+        if (blockIdx.x == 0) dev_tab[i] = x;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 64 && tag_mode != TAG_KEEP) reserve_tag_body(tag_blk, want, tag_mode);
+    __syncthreads();
+    if (with_schedule) schedule_body(tab_s, n_groups, T_total, n256, n128, tiles256, tiles128, key_lo, row_hi);
 }
 
 template <typename T>
@@ -355,31 +387,45 @@ inline int blocks_for_waves(int64_t waves) { return (int)((waves + 3) / 4); }
 
 }  // namespace
 
-hipError_t launch_schedule(const int* tab, int n_groups, int64_t total_tokens, int n256, int n128, TileDesc* tiles256,
-                           TileDesc* tiles128, int* key_lo, int* row_hi, hipStream_t s) {
+// Tag block, segment table and (bf16) schedule of a call: one launch when the table fits a kernel-argument
+// block, else the tag kernel, the table in pieces and the schedule kernel.
+hipError_t launch_prepare(const int32_t* host_words, int n_words, int* dev_tab, uint32_t* tag_block, const ReserveTag& tag,
+                          int tag_mode, bool with_schedule, int n_groups, int64_t total_tokens, int n256, int n128,
+                          const Schedule& sched, hipStream_t s) {
+    TileDesc* const t256 = (TileDesc*)sched.tiles256;
+    TileDesc* const t128 = (TileDesc*)sched.tiles128;
+    int* const key_lo = (int*)sched.key_lo;
+    int* const row_hi = (int*)sched.row_hi;
     int64_t n = total_tokens;
     if (n128 > n) n = n128;                            // n128 >= n256
-    hipLaunchKernelGGL(schedule_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, tab, n_groups, total_tokens,
-                       n256, n128, tiles256, tiles128, key_lo, row_hi);
-    return hipGetLastError();
-}
-
-hipError_t launch_reserve_tag(uint32_t* tag_block, const ReserveTag& tag, int mode, hipStream_t s) {
-    hipLaunchKernelGGL(reserve_tag_kernel, dim3(1), dim3(64), 0, s, tag_block, tag, mode);
-    return hipGetLastError();
-}
-
-hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s) {
-    for (int off = 0; off < n_words; off += TAB_CHUNK_WORDS) {
-        TabChunk c;
-        const int n = n_words - off < TAB_CHUNK_WORDS ? n_words - off : TAB_CHUNK_WORDS;
-        for (int i = 0; i < n; ++i) c.w[i] = host_words[off + i];
-        for (int i = n; i < TAB_CHUNK_WORDS; ++i) c.w[i] = 0;
-        hipLaunchKernelGGL(upload_table_kernel, dim3(1), dim3(256), 0, s, c, dev_tab, off, n);
+    const unsigned sched_blocks = (unsigned)((n + 255) / 256);
+    if (n_words <= PREP_WORDS) {
+        PrepChunk c;
+        for (int i = 0; i < n_words; ++i) c.w[i] = host_words[i];
+        for (int i = n_words; i < PREP_WORDS; ++i) c.w[i] = 0;
+        hipLaunchKernelGGL(prepare_kernel, dim3(with_schedule ? sched_blocks : 1u), dim3(256), 0, s, c, n_words, dev_tab,
+                           tag_block, tag, tag_mode, with_schedule ? 1 : 0, n_groups, total_tokens, n256, n128, t256, t128,
+                           key_lo, row_hi);
+        return hipGetLastError();
+    }
+    if (tag_mode != TAG_KEEP) {
+        hipLaunchKernelGGL(reserve_tag_kernel, dim3(1), dim3(64), 0, s, tag_block, tag, tag_mode);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    for (int off = 0; off < n_words; off += TAB_CHUNK_WORDS) {
+        TabChunk c;
+        const int nw = n_words - off < TAB_CHUNK_WORDS ? n_words - off : TAB_CHUNK_WORDS;
+        for (int i = 0; i < nw; ++i) c.w[i] = host_words[off + i];
+        for (int i = nw; i < TAB_CHUNK_WORDS; ++i) c.w[i] = 0;
+        hipLaunchKernelGGL(upload_table_kernel, dim3(1), dim3(256), 0, s, c, dev_tab, off, nw);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (with_schedule)
+        hipLaunchKernelGGL(schedule_kernel, dim3(sched_blocks), dim3(256), 0, s, (const int*)dev_tab, n_groups, total_tokens,
+                           n256, n128, t256, t128, key_lo, row_hi);
+    return hipGetLastError();
 }
 
 hipError_t launch_rowsum(const Problem& p, bool f32, hipStream_t s) {

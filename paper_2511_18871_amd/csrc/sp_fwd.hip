@@ -259,10 +259,21 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
     // checked after the fact: if a lane's 32 exponentials sum to more than P_LIMIT = 2^14 (or
     // to inf/NaN), the wave takes the exact row maximum as the new reference, rescales O and
     // the row sum, and recomputes this tile's P -- a rare path, taken a few times per row.
-    auto step = [&](int j, auto par_tag, f32x16 (&Scur)[2], f32x16 (&Snext)[2], const unsigned (&pbw)[16], unsigned (&pnew)[16]) {
+    // The LDS operands of the step's 32 MFMAs pass through one ring of RD registers that is read RD - 1
+    // MFMAs ahead without a break between the two products: a product that primed its own ring would
+    // start with an exposed LDS round trip.  Between the two steps of a barrier interval the ring is
+    // carried over as well (BRIDGE: the last slices fetch the first operands of the next step, whose V
+    // tile is resident; SECOND: the step finds them there): only the first step behind a barrier primes.
+    // (Priming right behind the barrier, ahead of the issue of the tile copies, measured the same.)
+    bf16x8 ring[RD];
+    auto step = [&](int j, auto par_tag, auto second_tag, auto bridge_tag, f32x16 (&Scur)[2], f32x16 (&Snext)[2],
+                    const unsigned (&pbw)[16], unsigned (&pnew)[16]) {
         constexpr int R = decltype(par_tag)::value;
+        constexpr bool SECOND = decltype(second_tag)::value, BRIDGE = decltype(bridge_tag)::value;
+        constexpr int OFF = SECOND ? 32 % RD : 0;     // ring position of this step's first operand
         const char* ldsV = ldsVb[(R + NB - 1) % NB];  // V(j-1)
         const char* ldsK = ldsKb[(R + 1) % NB];       // K(j+1)
+        const char* ldsVn = ldsVb[R % NB];            // V(j), the next step's
         if (needs_mask(j)) mask(j, Scur);
         __builtin_amdgcn_sched_barrier(0);
         const float mc = m * cs;
@@ -278,31 +289,27 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
             if (e >= 2 && (e & 1) == 0) { pnew[(e - 2) >> 1] = pack2(pe[e - 2], pe[e - 1]); asm volatile("" : "+v"(pnew[(e - 2) >> 1])); }
             if (e >= 3 && (e & 1) == 1) { tsr = sum2(pnew[(e - 3) >> 1], tsr); asm volatile("" : "+v"(tsr)); }
         };
-        {   // O^T += V(j-1)^T P(j-1)^T, P operand outermost so that its registers die early
-            s16x4 ring[RD][2];
+        // operand of slice i: 0..15 the V^T pieces of O^T += V(j-1)^T P(j-1)^T, 16..31 the K rows of
+        // S(j+1) = K(j+1) Q^T, 32.. the next step's first V^T pieces
+        auto fetch = [&](int i) -> bf16x8 {
+            if (i < 16) return cat4(ldV(ldsV, i, 0), ldV(ldsV, i, 1));
+            if (i < 32) return ldK(ldsK, i - 16);
+            return cat4(ldV(ldsVn, i - 32, 0), ldV(ldsVn, i - 32, 1));
+        };
+        if (!SECOND) {
 #pragma unroll
-            for (int i = 0; i < RD - 1; ++i) { ring[i][0] = ldV(ldsV, i, 0); ring[i][1] = ldV(ldsV, i, 1); }
+            for (int i = 0; i < RD - 1; ++i) ring[i] = fetch(i);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (i + RD - 1 < 16) { ring[(i + RD - 1) % RD][0] = ldV(ldsV, i + RD - 1, 0); ring[(i + RD - 1) % RD][1] = ldV(ldsV, i + RD - 1, 1); }
-                oacc[i & 3] = mfma32(cat4(ring[i % RD][0], ring[i % RD][1]), pbop(pbw, i >> 3, (i >> 2) & 1), oacc[i & 3]);
-                valu(i);
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
-        {   // S(j+1) = K(j+1) Q^T
-            bf16x8 ring[RD];
 #pragma unroll
-            for (int i = 0; i < RD - 1; ++i) ring[i] = ldK(ldsK, i);
+        for (int i = 0; i < 32; ++i) {
+            if (i + RD - 1 < 32 || BRIDGE) ring[(i + RD - 1 + OFF) % RD] = fetch(i + RD - 1);
+            if (i < 16)     // P operand outermost so that its registers die early
+                oacc[i & 3] = mfma32(ring[(i + OFF) % RD], pbop(pbw, i >> 3, (i >> 2) & 1), oacc[i & 3]);
+            else
+                Snext[(i - 16) >> 3] = mfma32(ring[(i + OFF) % RD], qreg[i & 7], (i & 7) == 0 ? zero16 : Snext[(i - 16) >> 3]);
+            valu(i);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (i + RD - 1 < 16) ring[(i + RD - 1) % RD] = ldK(ldsK, i + RD - 1);
-                Snext[i >> 3] = mfma32(ring[i % RD], qreg[i & 7], (i & 7) == 0 ? zero16 : Snext[i >> 3]);
-                valu(16 + i);
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
         tsum += pe[31];
         pnew[15] = pack2(pe[30], pe[31]);
@@ -385,16 +392,16 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
             issue(vbase_s, m0V[2], j + 2);
             issue(kbase_s, m0K[3], j + 3);
             issue(kbase_s, m0K[0], j + 4);
-            step(j, std::integral_constant<int, 0>{}, sA, sB, pbA, pbB);
-            step(j + 1, std::integral_constant<int, 1>{}, sB, sA, pbB, pbA);
+            step(j, std::integral_constant<int, 0>{}, std::false_type{}, std::true_type{}, sA, sB, pbA, pbB);
+            step(j + 1, std::integral_constant<int, 1>{}, std::true_type{}, std::false_type{}, sB, sA, pbB, pbA);
             wait_vm0();
             __syncthreads();
             issue(vbase_s, m0V[3], j + 3);
             issue(vbase_s, m0V[0], j + 4);
             issue(kbase_s, m0K[1], j + 5);
             issue(kbase_s, m0K[2], j + 6);
-            step(j + 2, std::integral_constant<int, 2>{}, sA, sB, pbA, pbB);
-            step(j + 3, std::integral_constant<int, 3>{}, sB, sA, pbB, pbA);
+            step(j + 2, std::integral_constant<int, 2>{}, std::false_type{}, std::true_type{}, sA, sB, pbA, pbB);
+            step(j + 3, std::integral_constant<int, 3>{}, std::true_type{}, std::false_type{}, sB, sA, pbB, pbA);
         }
     } else {
         // One step per barrier.  At the barrier before step j the tiles V(j-1) and K(j+1) are resident
@@ -406,12 +413,12 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
             __syncthreads();
             issue(vbase_s, m0V[0], j);
             issue(kbase_s, m0K[0], j + 2);
-            step(j, std::integral_constant<int, 0>{}, sA, sB, pbA, pbB);
+            step(j, std::integral_constant<int, 0>{}, std::false_type{}, std::false_type{}, sA, sB, pbA, pbB);
             wait_vm0();
             __syncthreads();
             issue(vbase_s, m0V[1], j + 1);
             issue(kbase_s, m0K[1], j + 3);
-            step(j + 1, std::integral_constant<int, 1>{}, sB, sA, pbB, pbA);
+            step(j + 1, std::integral_constant<int, 1>{}, std::false_type{}, std::false_type{}, sB, sA, pbB, pbA);
         }
     }
     wait_vm0();

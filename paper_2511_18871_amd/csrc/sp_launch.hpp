@@ -20,6 +20,7 @@ struct ReserveTag { uint32_t w[TAG_WORDS]; };
 // reserve that `tag` describes.  TAG_CHECK: a backward asks whether the workspace holds exactly the
 // reserve `tag` describes; if not, the tag is cleared (the call is about to write into the workspace).
 constexpr int TAG_CLEAR = 0, TAG_WRITE = 1, TAG_CHECK = 2;
+constexpr int TAG_KEEP = -1;      // for launch_prepare: leave the tag block as it is
 
 struct Problem {
     const void* q; const void* k; const void* v;
@@ -74,10 +75,9 @@ hipError_t launch_logprob_bwd(const void* z, const int* y, const float* lse, con
 hipError_t launch_grpo(const float* logp, const float* old, const float* ref, const float* adv, float* g,
                        float* J, float* loss, const int* tab, int n_resp, int n_nonempty, float eps_low,
                        float eps_high, float beta, hipStream_t s);
-hipError_t launch_reserve_tag(uint32_t* tag_block, const ReserveTag& tag, int mode, hipStream_t s);
-hipError_t launch_schedule(const int* tab, int n_groups, int64_t total_tokens, int n256, int n128, TileDesc* tiles256,
-                           TileDesc* tiles128, int* key_lo, int* row_hi, hipStream_t s);
-hipError_t launch_upload_table(const int32_t* host_words, int n_words, int* dev_tab, hipStream_t s);
+hipError_t launch_prepare(const int32_t* host_words, int n_words, int* dev_tab, uint32_t* tag_block, const ReserveTag& tag,
+                          int tag_mode, bool with_schedule, int n_groups, int64_t total_tokens, int n256, int n128,
+                          const Schedule& sched, hipStream_t s);
 
 // Packings whose 256-row workgroups would run fewer 64-key steps than this on average take the kernels'
 // 128-row shape (two workgroups per CU).  SP_ATTN_SMALL_STEPS overrides the default, for measurements.
