@@ -67,6 +67,32 @@ def test_random_batches_every_element(seed):
     print(gate("dV", to64(dv), rdv, w.dtype))
 
 
+# A segment table of up to 896 words is handed to the kernels in one preparation launch (tag block, table and
+# schedule together, the schedule computed from a copy of the table in LDS); longer ones take the separate
+# kernels, and more than 960 words several upload launches.  Word count = 4 + 8 per group + (G + 1) per group.
+@pytest.mark.parametrize("extra_responses,want_words", [(0, 895), (1, 896), (2, 897), (65, 960), (66, 961)])
+@pytest.mark.parametrize("dtype,head_dim", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_table_sizes_around_the_one_launch_limit(extra_responses, want_words, dtype, head_dim):
+    rng = np.random.default_rng(100 + extra_responses)
+    groups = [W.Group(int(rng.integers(0, 70)), [int(rng.integers(0, 40)) for _ in range(2)]) for _ in range(80)]
+    groups.append(W.Group(int(rng.integers(1, 70)), [int(rng.integers(0, 40)) for _ in range(2 + extra_responses)]))
+    groups = [g if g.prompt_len + sum(g.resp_lens) > 0 else W.Group(1, g.resp_lens) for g in groups]
+    w = W.Workload(f"limit{extra_responses}", groups, 4, 2, head_dim, dtype, 7100 + extra_responses)
+    pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
+    assert len(B.sp_attn_segment_table(pl, Gs, rl)) == want_words
+    t = W.make_tensors(w)
+    q, k, v, d_o = t.q.cuda(), t.k.cuda(), t.v.cuda(), t.d_o.cuda()
+    o, lse = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, sc)
+    dq, dk, dv = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc)
+    torch.cuda.synchronize()
+    rdq, rdk, rdv, ro, rlse = oracle_bwd(w, t)
+    print(gate("O", to64(o), ro, dtype))
+    gate_lse(to64(lse), rlse, dtype)
+    print(gate("dQ", to64(dq), rdq, dtype))
+    print(gate("dK", to64(dk), rdk, dtype))
+    print(gate("dV", to64(dv), rdv, dtype))
+
+
 def test_tensors_beyond_4_gib_sampled_groups():
     """1100 groups, 1.1e6 tokens, 32 q / 16 kv heads: q, o, dO, dq are 9 GB each (element index up to
     4.5e9), k, v, dk, dv 4.5 GB each.  Groups are independent, so the oracle on one group's slice
