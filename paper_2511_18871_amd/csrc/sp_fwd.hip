@@ -452,13 +452,18 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
                 for (int e = 0; e < 4; ++e) x[e] = value(db, 4 * gq + e);
                 *reinterpret_cast<bf16x4*>(stage + tile_off(c, 4 * db + gq) + 8 * hh) = x;
             }
+        // all eight reads first, then the stores (one LDS round trip instead of eight); the rows of one lane lie
+        // four rows apart, so one 64-bit address and a constant stride serve all of them
+        bf16x8 x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = lds_read_row8(stage, 4 * i + (l >> 4), l & 15);
+        __builtin_amdgcn_sched_barrier(0);
+        __bf16* const p0 = dst + ((int64_t)(gd.tok_base + tw0 + (l >> 4)) * a.Hq + head) * 128 + 8 * (l & 15);
+        const int64_t stride = (int64_t)4 * a.Hq * 128;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int r = 4 * i + (l >> 4);
-            const bf16x8 x = lds_read_row8(stage, r, l & 15);
-            const int tr = tw0 + r;
-            if (tr < Tg && !(a.resp_only && tr < Lp))
-                *reinterpret_cast<bf16x8*>(dst + ((int64_t)(gd.tok_base + tr) * a.Hq + head) * 128 + 8 * (l & 15)) = x;
+            const int tr = tw0 + 4 * i + (l >> 4);
+            if (tr < Tg && !(a.resp_only && tr < Lp)) *reinterpret_cast<bf16x8*>(p0 + i * stride) = x[i];
         }
     };
     store_rows(ao, [&](int db, int r) { return (__bf16)(oacc[db][r] * inv); });
