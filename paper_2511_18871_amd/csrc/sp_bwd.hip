@@ -46,17 +46,26 @@ struct BwdArgs {
 // ------------------------------------------------------------------------------------
 // dq pass
 // ------------------------------------------------------------------------------------
+//
+// Two shapes of workgroup, as in the forward.  NW = 8: 256 rows, a ring of three slots of a whole 64-key tile
+// (K and V: 96 KB), one workgroup per CU, one barrier per tile.  NW = 4: 128 rows, a ring of four slots of HALF
+// a tile (32 keys of K and V: 64 KB), one barrier per half, two workgroups per CU: for packings whose key
+// loops are short, where a workgroup's fixed costs (a quarter of its life with one workgroup per CU) then
+// overlap with the other workgroup's loop and fewer rows ride along through tiles they cannot see.
 template <int NW>
-__global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
+__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(BwdArgs a) {
     constexpr int BM = 32 * NW, BN = 64;
     constexpr int RD = 3;                       // LDS operand ring depth (prefetch distance RD - 1 MFMAs)
     constexpr int NE1 = 5;                      // elements of a half's vector work done under the previous D stage
-    static_assert(NW == 8, "the copy split below assumes eight waves");
-    __shared__ __attribute__((aligned(1024))) char lds[3][2 * TILE_BYTES];   // [ring slot][K | V]
+    static_assert(NW == 8 || NW == 4, "the copy split below assumes eight or four waves");
+    constexpr int NSLOT = NW == 8 ? 3 : 4;
+    constexpr int SLOT_BYTES = NW == 8 ? 2 * TILE_BYTES : TILE_BYTES;       // [K | V] of 64 keys, or of 32
+    constexpr int V_OFF = SLOT_BYTES / 2;                                    // where V starts inside a slot
+    __shared__ __attribute__((aligned(1024))) char lds[NSLOT][SLOT_BYTES];
 
     int tile, head;
     if (!decode_item(blockIdx.x, a.n_tiles, a.Hq, a.Hkv, tile, head)) return;
-    const TileDesc td = a.sched.tiles256[tile];     // BM == 256
+    const TileDesc td = (BM == 256 ? a.sched.tiles256 : a.sched.tiles128)[tile];
     const int ti = td.ti;
     GroupDesc gd;
     gd.tok_base = td.tok_base; gd.Lp = td.Lp; gd.Tg = td.Tg; gd.G = 0; gd.roff = nullptr;
@@ -148,11 +157,14 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     // copies chunks 4w .. 4w+3 (4 rows each) of the K tile and of the V tile.  Rows past the
     // group's end re-read its last row (those keys are always masked; values must be finite).
     const unsigned stride_b = (unsigned)(kv_stride * 2);
+    // (NW = 4: every wave is the first of its SIMD within the workgroup; wave w copies chunks 2w, 2w+1 of the
+    // 32 rows of K and of V of a half.)
     const bool copier = w < 4;
-    unsigned voff[4];
+    constexpr int NCH = NW == 8 ? 4 : 2;        // chunks of K (and of V) a copying wave moves per slot
+    unsigned voff[NCH];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int row = 4 * (4 * (w & 3) + u) + (l >> 4);
+    for (int u = 0; u < NCH; ++u) {
+        const int row = 4 * (NCH * (w & 3) + u) + (l >> 4);
         voff[u] = row * stride_b + (((l & 15) ^ swz(row)) << 4);
     }
     auto sgpr64 = [](const void* p) -> uint64_t {
@@ -161,31 +173,35 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
                (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
     };
     const uint64_t kbase_s = sgpr64(kbase), vbase_s = sgpr64(vbase);
-    const unsigned tile_bytes = BN * stride_b;
     auto lds_u32 = [](char* p) -> unsigned {
         return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)p);
     };
-    const unsigned m0slot[3] = {lds_u32(lds[0]) + 4096u * (w & 3), lds_u32(lds[1]) + 4096u * (w & 3),
-                                lds_u32(lds[2]) + 4096u * (w & 3)};
+    unsigned m0slot[NSLOT];
+#pragma unroll
+    for (int i = 0; i < NSLOT; ++i) m0slot[i] = lds_u32(lds[i]) + 1024u * NCH * (w & 3);
     auto tile_at = [&](int it) { return it < n1 ? it : k2b + (it - n1); };
+    // NW = 8: `it` counts 64-key tiles; NW = 4: halves of them (32 keys), each into a slot of its own
     auto issue = [&](int it, int slot) {
-        if (!copier || it >= total) return;
-        const int kt = tile_at(it);
-        const uint64_t off = (uint64_t)(unsigned)kt * tile_bytes;
+        if (!copier || it >= (NW == 8 ? total : 2 * total)) return;
+        // first key of the slot; the second half of a group's last tile may lie wholly past the group's end: it
+        // is then read from the group's last row on (every offset below stays non-negative)
+        const int key0 = min(NW == 8 ? tile_at(it) * BN : tile_at(it >> 1) * BN + 32 * (it & 1), Tg - 1);
+        constexpr int ROWS = NW == 8 ? BN : 32;
+        const uint64_t off = (uint64_t)(unsigned)key0 * stride_b;
         const unsigned m0 = m0slot[slot];
-        if (kt * BN + BN <= Tg) {
+        if (key0 + ROWS <= Tg) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) async_copy16_sm(kbase_s + off, voff[u], m0 + 1024u * u);
+            for (int u = 0; u < NCH; ++u) async_copy16_sm(kbase_s + off, voff[u], m0 + 1024u * u);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) async_copy16_sm(vbase_s + off, voff[u], m0 + TILE_BYTES + 1024u * u);
+            for (int u = 0; u < NCH; ++u) async_copy16_sm(vbase_s + off, voff[u], m0 + V_OFF + 1024u * u);
         } else {
-            const int last = Tg - 1 - kt * BN;
+            const int last = Tg - 1 - key0;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int row = 4 * (4 * (w & 3) + u) + (l >> 4);
+            for (int u = 0; u < NCH; ++u) {
+                const int row = 4 * (NCH * (w & 3) + u) + (l >> 4);
                 const unsigned vo = min(row, last) * stride_b + (((l & 15) ^ swz(row)) << 4);
                 async_copy16_sm(kbase_s + off, vo, m0 + 1024u * u);
-                async_copy16_sm(vbase_s + off, vo, m0 + TILE_BYTES + 1024u * u);
+                async_copy16_sm(vbase_s + off, vo, m0 + V_OFF + 1024u * u);
             }
         }
     };
@@ -226,7 +242,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
         }
     };
     auto ldm = [&](const char* slot, int half, int i) {      // operand i of M: K rows for i < 8 (S), V rows after (dP)
-        return lds_read_row8(slot + ((i & 8) ? TILE_BYTES : 0), 32 * half + c, 2 * (i & 7) + hh);
+        return lds_read_row8(slot + ((i & 8) ? V_OFF : 0), 32 * half + c, 2 * (i & 7) + hh);
     };
     auto ldd = [&](const char* slot, int half, int i, int part) {   // MFMA i of D: db = i / 2, 16-key step mm = i % 2
         const int col4 = 32 * (i >> 1) + 16 * c16 + 4 * (j & 3);
@@ -308,6 +324,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
     if (total > 0) {
         issue(0, 0);
         issue(1, 1);
+        if constexpr (NW == 4) issue(2, 2);
         wait_vm0();
         __syncthreads();
         // M(0) and the first NE1 elements of V(0), unpipelined
@@ -319,6 +336,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
         if (needs_mask(0)) mask(0, SA, PA);
 #pragma unroll
         for (int r = 0; r < NE1; ++r) v_consume(SA, PA, r, v_issue(SA, r));
+        if constexpr (NW == 8) {
         int slot = 0;
         for (int it = 0; it < total; ++it) {
             const int slot1 = slot == 2 ? 0 : slot + 1, slot2 = slot == 0 ? 2 : slot - 1;
@@ -327,6 +345,22 @@ __global__ __launch_bounds__(NW * 64) void bwd_dq_kernel(BwdArgs a) {
             stage(2 * it, SA, PA, SB, PB, lds[slot], 1, lds[slot], 0);
             stage(2 * it + 1, SB, PB, SA, PA, lds[slot1], 0, lds[slot], 1);
             slot = slot1;
+        }
+        } else {
+        // Half h lives in slot h % 4.  Stage h reads the slots of h + 1 (M) and h (D); at the barrier in
+        // front of it every wave has left stage h - 1, whose D read the slot of h - 1 = the slot of h + 3,
+        // which is issued then: two stages ahead of the M that needs it.
+        // (Leaving the half issued at the previous barrier in flight across the barrier, vmcnt(4) instead of
+        // vmcnt(0), measured the same: the other workgroup of the CU covers the wait.)
+        for (int h = 0; h < H; h += 2) {
+            if (h > 0) { wait_vm0(); __syncthreads(); }
+            issue(h + 3, (h + 3) & 3);
+            stage(h, SA, PA, SB, PB, lds[(h + 1) & 3], 0, lds[h & 3], 0);
+            wait_vm0();
+            __syncthreads();
+            issue(h + 4, h & 3);
+            stage(h + 1, SB, PB, SA, PA, lds[(h + 2) & 3], 0, lds[(h + 1) & 3], 0);
+        }
         }
     }
 
@@ -766,10 +800,12 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     a.tab = p.tab; a.sched = p.sched; a.n_groups = p.n_groups; a.Hq = p.Hq; a.Hkv = p.Hkv; a.scale = p.scale; a.c = p.scale * LOG2E;
     a.resp_only = p.resp_only; a.accumulate = p.accumulate;
     if (p.stages & STAGE_DQ) {
-        constexpr int NWQ = 8;
-        a.n_tiles = count_tiles(p, 32 * NWQ);
+        // short key loops: the 128-row shape, two workgroups per CU (the forward's rule, see bwd_dq_kernel)
+        const bool small = mean_key_steps(p) < (double)small_shape_steps();
+        a.n_tiles = count_tiles(p, small ? 128 : 256);
         const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
-        hipLaunchKernelGGL(bwd_dq_kernel<NWQ>, dim3(grid), dim3(NWQ * 64), 0, s, a);
+        if (small) hipLaunchKernelGGL(bwd_dq_kernel<4>, dim3(grid), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(bwd_dq_kernel<8>, dim3(grid), dim3(512), 0, s, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         e = launch_short_rows(p, true, s);

@@ -478,31 +478,6 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
 
 }  // namespace
 
-// Mean number of 64-key steps that a 256-row workgroup of this packing runs (host arithmetic on the
-// segment table): the measure by which the workgroup shape is chosen.
-static double mean_key_steps(const Problem& p) {
-    const int32_t* tab = p.host_table;
-    int64_t steps = 0, tiles = 0;
-    for (int g = 0; g < p.n_groups; ++g) {
-        const int32_t* e = tab + TAB_HEADER + TAB_GROUP_WORDS * g;
-        const int Lp = e[1], Tg = e[2], G = e[4];
-        const int32_t* roff = tab + e[3];
-        for (int t0 = 0; t0 < Tg; t0 += 256, ++tiles) {
-            const int t1 = t0 + 256 < Tg ? t0 + 256 : Tg;
-            const int n1 = ((Lp < t1 ? Lp : t1) + BN - 1) / BN;
-            steps += n1;
-            if (t1 > Lp) {
-                const int first = t0 > Lp ? t0 : Lp;          // first response row: its segment start opens the range
-                int lo = 0, hi = G;
-                while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (roff[mid] <= first) lo = mid; else hi = mid; }
-                const int k2b = roff[lo] / BN > n1 ? roff[lo] / BN : n1;
-                steps += (t1 + BN - 1) / BN - k2b;
-            }
-        }
-    }
-    return tiles ? (double)steps / (double)tiles : 0.0;
-}
-
 hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
     FwdArgs a{};
     const int n_sets = p.n_sets > 1 ? p.n_sets : 1;

@@ -83,6 +83,32 @@ hipError_t launch_prepare(const int32_t* host_words, int n_words, int* dev_tab, 
 // 128-row shape (two workgroups per CU).  SP_ATTN_SMALL_STEPS overrides the default, for measurements.
 int small_shape_steps();
 
+// Mean number of 64-key steps that a 256-row workgroup of this packing runs (host arithmetic on the
+// segment table): the measure by which the workgroup shape is chosen.
+inline double mean_key_steps(const Problem& p) {
+    const int32_t* tab = p.host_table;
+    int64_t steps = 0, tiles = 0;
+    for (int g = 0; g < p.n_groups; ++g) {
+        const int32_t* e = tab + TAB_HEADER + TAB_GROUP_WORDS * g;
+        const int Lp = e[1], Tg = e[2], G = e[4];
+        const int32_t* roff = tab + e[3];
+        for (int t0 = 0; t0 < Tg; t0 += 256, ++tiles) {
+            const int t1 = t0 + 256 < Tg ? t0 + 256 : Tg;
+            const int n1 = ((Lp < t1 ? Lp : t1) + 63) / 64;
+            steps += n1;
+            if (t1 > Lp) {
+                const int first = t0 > Lp ? t0 : Lp;          // first response row: its segment start opens the range
+                int lo = 0, hi = G;
+                while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (roff[mid] <= first) lo = mid; else hi = mid; }
+                const int k2b = roff[lo] / 64 > n1 ? roff[lo] / 64 : n1;
+                steps += (t1 + 63) / 64 - k2b;
+            }
+        }
+    }
+    return tiles ? (double)steps / (double)tiles : 0.0;
+}
+
+
 // Packings that the bandwidth-shaped bf16 rowsum kernel takes (its per-head sums of 16 tokens fit its LDS)
 inline bool rowsum_fast_path(const Problem& p) { return p.head_dim == 128 && (size_t)p.Hq * 16 * sizeof(float) <= 32768; }
 

@@ -49,6 +49,43 @@ def test_random_packing_fwd_bwd(seed):
     gate("dV " + desc, to64(dv), rdv, w.dtype)
 
 
+# Both workgroup shapes of the forward and of the dq pass (256 rows, whole 64-key tiles; 128 rows, half tiles, two
+# workgroups per CU), each forced on packings the library would give to the other: a group's last tile may end
+# in its first half, so that the 128-row shape's copy of the second half lies wholly past the group's end.
+@pytest.mark.parametrize("steps", [0, 1 << 20])
+@pytest.mark.parametrize("seed", [2, 5, 11, 360, 1306])
+def test_random_packing_both_workgroup_shapes(seed, steps):
+    try:
+        B.set_small_shape_steps(steps)
+        test_random_packing_fwd_bwd(seed)
+    finally:
+        B.set_small_shape_steps(-1)
+
+
+@pytest.mark.parametrize("steps", [0, 1 << 20])
+@pytest.mark.parametrize("tail", [1, 31, 32, 33, 63, 64])
+def test_group_end_inside_either_half_of_the_last_tile(tail, steps):
+    """Group lengths 256 + tail and 128 + tail: the last key tile ends after `tail` keys."""
+    groups = [W.Group(200, [56 + tail]), W.Group(0, [128 + tail]), W.Group(64 + tail, [])]
+    w = W.Workload(f"tail{tail}", groups, 4, 2, 128, torch.bfloat16, 500 + tail)
+    t = W.make_tensors(w)
+    pl, Gs, rl, sc = w.prompt_lens(), w.Gs(), w.resp_lens_flat(), w.softmax_scale
+    q, k, v, d_o = t.q.cuda(), t.k.cuda(), t.v.cuda(), t.d_o.cuda()
+    try:
+        B.set_small_shape_steps(steps)
+        o, lse = B.sp_attn_fwd_batched(q, k, v, pl, Gs, rl, sc)
+        dq, dk, dv = B.sp_attn_bwd_batched(q, k, v, o, lse, d_o, pl, Gs, rl, sc)
+        torch.cuda.synchronize()
+    finally:
+        B.set_small_shape_steps(-1)
+    rdq, rdk, rdv, ro, rlse = oracle_bwd(w, t)
+    gate("O", to64(o), ro, w.dtype)
+    gate_lse(to64(lse), rlse, w.dtype)
+    gate("dQ", to64(dq), rdq, w.dtype)
+    gate("dK", to64(dk), rdk, w.dtype)
+    gate("dV", to64(dv), rdv, w.dtype)
+
+
 @pytest.mark.parametrize("heads", [(6, 3), (12, 12), (10, 5), (48, 24)])
 def test_kv_head_counts_that_neither_divide_nor_are_a_multiple_of_8(heads):
     """Such head counts take the plain block -> (tile, head) mapping instead of the XCD-aware ones."""
