@@ -19,7 +19,7 @@
 static __device__ __align__(256) unsigned char scratch[SP_STATIC_SCRATCH_BYTES_IMPL];
 
 namespace sp {
-namespace { std::atomic<int> g_small_steps{40}; }
+namespace { std::atomic<int> g_small_steps{-1}; }      // < 0: the rule of use_small_shape()
 int small_shape_steps() { return g_small_steps.load(std::memory_order_relaxed); }
 }  // namespace sp
 
@@ -562,7 +562,7 @@ sp_status sp_attn_bwd_batched_static(const void* q, const void* k, const void* v
 }
 
 void sp_attn_set_small_shape_steps(int32_t steps) {
-    sp::g_small_steps.store(steps < 0 ? 40 : steps, std::memory_order_relaxed);
+    sp::g_small_steps.store(steps < 0 ? -1 : steps, std::memory_order_relaxed);
 }
 
 const char* sp_attn_last_error(void) { return g_err; }

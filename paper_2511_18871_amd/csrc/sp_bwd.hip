@@ -801,7 +801,7 @@ hipError_t launch_bwd_bf16(const Problem& p, hipStream_t s) {
     a.resp_only = p.resp_only; a.accumulate = p.accumulate;
     if (p.stages & STAGE_DQ) {
         // short key loops: the 128-row shape, two workgroups per CU (the forward's rule, see bwd_dq_kernel)
-        const bool small = mean_key_steps(p) < (double)small_shape_steps();
+        const bool small = use_small_shape(p);
         a.n_tiles = count_tiles(p, small ? 128 : 256);
         const int grid = grid_for_items(a.n_tiles, p.Hq, p.Hkv);
         if (small) hipLaunchKernelGGL(bwd_dq_kernel<4>, dim3(grid), dim3(256), 0, s, a);

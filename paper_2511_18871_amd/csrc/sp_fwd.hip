@@ -492,7 +492,7 @@ hipError_t launch_fwd_bf16(const Problem& p, hipStream_t s) {
     a.o_lo = n_sets == 1 ? (__bf16*)p.o_lo_out : nullptr;
     // Short key loops: the 128-row shape, two workgroups per CU (see fwd_kernel).  The naive baseline keeps
     // the 256-row shape whatever the packing (its loops are long by construction).
-    const bool small = !p.naive && mean_key_steps(p) < (double)small_shape_steps();
+    const bool small = !p.naive && use_small_shape(p);
     const int bm = small ? 128 : 256;
     a.n_tiles = count_tiles(p, bm);
     a.blocks_per_set = grid_for_items(a.n_tiles, p.Hq, p.Hkv);

@@ -83,17 +83,17 @@ hipError_t launch_prepare(const int32_t* host_words, int n_words, int* dev_tab, 
 // 128-row shape (two workgroups per CU).  SP_ATTN_SMALL_STEPS overrides the default, for measurements.
 int small_shape_steps();
 
-// Mean number of 64-key steps that a 256-row workgroup of this packing runs (host arithmetic on the
-// segment table): the measure by which the workgroup shape is chosen.
-inline double mean_key_steps(const Problem& p) {
+// Number of 64-key steps that the workgroups of this packing run with row tiles of `bm` rows (per q head; host
+// arithmetic on the segment table), and the number of such workgroups.
+inline void key_steps(const Problem& p, int bm, int64_t& steps, int64_t& tiles) {
     const int32_t* tab = p.host_table;
-    int64_t steps = 0, tiles = 0;
+    steps = 0; tiles = 0;
     for (int g = 0; g < p.n_groups; ++g) {
         const int32_t* e = tab + TAB_HEADER + TAB_GROUP_WORDS * g;
         const int Lp = e[1], Tg = e[2], G = e[4];
         const int32_t* roff = tab + e[3];
-        for (int t0 = 0; t0 < Tg; t0 += 256, ++tiles) {
-            const int t1 = t0 + 256 < Tg ? t0 + 256 : Tg;
+        for (int t0 = 0; t0 < Tg; t0 += bm, ++tiles) {
+            const int t1 = t0 + bm < Tg ? t0 + bm : Tg;
             const int n1 = ((Lp < t1 ? Lp : t1) + 63) / 64;
             steps += n1;
             if (t1 > Lp) {
@@ -105,7 +105,21 @@ inline double mean_key_steps(const Problem& p) {
             }
         }
     }
-    return tiles ? (double)steps / (double)tiles : 0.0;
+}
+
+// Which workgroup shape the forward and the dq pass take.  The 128-row shape executes less work that no row
+// of a tile needs (fewer rows ride along through the key tiles of other responses and past their own
+// diagonal) and overlaps the fixed costs of two workgroups per CU, but pays for it: twice the tile copies per
+// MFMA and a barrier per step.  Measured on packings from 3 K to 270 K tokens the price is about 3.5 % of
+// the loop, so the small shape is taken when it saves more executed steps than that.  The knob, when set,
+// replaces the rule by a threshold on the mean number of steps of a 256-row workgroup.
+inline bool use_small_shape(const Problem& p) {
+    int64_t s256, t256, s128, t128;
+    key_steps(p, 256, s256, t256);
+    const int knob = small_shape_steps();
+    if (knob >= 0) return t256 > 0 && (double)s256 / (double)t256 < (double)knob;
+    key_steps(p, 128, s128, t128);
+    return 0.5 * (double)s128 * 1.035 < (double)s256;
 }
 
 
