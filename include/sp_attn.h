@@ -379,7 +379,7 @@ sp_status sp_attn_probe_atomic_add(float* buf, int64_t rows, int32_t heads, int3
  * shapes: 256 query rows with one workgroup per CU, for long key loops, and 128 rows with two
  * workgroups per CU, whose fixed per-workgroup costs overlap and which execute less work that no row of
  * a tile needs, for batches of short or ragged groups.  By default a call (forward, dq pass) takes the
- * small shape when that saves more than 3.5 % of the executed 64-key steps (host arithmetic on the
+ * small shape when that saves more than 3 % of the executed 64-key steps (host arithmetic on the
  * lengths).  With the knob set, it takes the small shape when a 256-row workgroup of its packing would run
  * fewer than `steps` such steps on average: 0 = always the large shape; a large value = always the small
  * one; negative = back to the default rule.  Results do not depend on the shape beyond rounding order.

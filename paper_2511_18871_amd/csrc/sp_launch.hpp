@@ -110,7 +110,7 @@ inline void key_steps(const Problem& p, int bm, int64_t& steps, int64_t& tiles) 
 // Which workgroup shape the forward and the dq pass take.  The 128-row shape executes less work that no row
 // of a tile needs (fewer rows ride along through the key tiles of other responses and past their own
 // diagonal) and overlaps the fixed costs of two workgroups per CU, but pays for it: twice the tile copies per
-// MFMA and a barrier per step.  Measured on packings from 3 K to 270 K tokens the price is about 3.5 % of
+// MFMA and a barrier per step.  Measured on packings from 3 K to 270 K tokens the price is about 3 % of
 // the loop, so the small shape is taken when it saves more executed steps than that.  The knob, when set,
 // replaces the rule by a threshold on the mean number of steps of a 256-row workgroup.
 inline bool use_small_shape(const Problem& p) {
@@ -119,7 +119,7 @@ inline bool use_small_shape(const Problem& p) {
     const int knob = small_shape_steps();
     if (knob >= 0) return t256 > 0 && (double)s256 / (double)t256 < (double)knob;
     key_steps(p, 128, s128, t128);
-    return 0.5 * (double)s128 * 1.035 < (double)s256;
+    return 0.5 * (double)s128 * 1.03 < (double)s256;
 }
 
 
