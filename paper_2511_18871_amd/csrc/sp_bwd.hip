@@ -89,17 +89,71 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(BwdArgs a) {
     // lanes 0..31 hold the wave's rows in order: the last valid row's start comes from its lane
     const int st_last = wave_valid ? __builtin_amdgcn_readlane(st, tw1 - tw0) : 0;
 
+    auto sgpr64 = [](const void* p) -> uint64_t {
+        const uint64_t b = (uint64_t)(uintptr_t)p;
+        return ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+               (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    };
+    auto lds_u32 = [](char* p) -> unsigned {
+        return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)p);
+    };
+
+    // The wave's rows of q and dO (and of o and its residual for the folded rowsum) in MFMA operand layout.
+    // Loaded straight from memory in that layout an instruction touches 32 rows and uses 32 bytes of each,
+    // and the 32 such instructions of a wave are bound by the address unit: a quarter of a 128-row workgroup's
+    // life on short key loops.  They come in like the K/V tiles instead: copied row-contiguous (four whole
+    // rows per instruction) into the wave's own share of the not yet used tile ring, swizzled, and read back
+    // with the operand reads of a K tile.  The share holds TPR tensors of 32 rows at a time.  Rows past the
+    // end of the group read the group's last row: their scores are all masked (P = dS = 0 whatever q and dO
+    // hold, and a non-finite dO there only reaches dq rows that are not stored).
+    constexpr int SHARE = NSLOT * SLOT_BYTES / NW;          // 16 KB (NW = 4), 12 KB (NW = 8)
+    constexpr int TPR = SHARE / 8192;
+    char* const stg = &lds[0][0] + SHARE * w;
+    const int rbase = min(tw0, Tg - 1), rlast = Tg - 1 - rbase;
+    auto stage_rows = [&](const __bf16* tensor, int slot) {
+        const uint64_t sb = sgpr64(tensor + ((int64_t)(gd.tok_base + rbase) * a.Hq + head) * 128);
+        const unsigned m0 = lds_u32(stg) + 8192u * slot;
+        const unsigned row_bytes = (unsigned)a.Hq * 256u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int row = 4 * u + (l >> 4);
+            async_copy16_sm(sb, (unsigned)min(row, rlast) * row_bytes + (((l & 15) ^ swz(row)) << 4), m0 + 1024u * u);
+        }
+    };
+    auto read_rows = [&](int slot, bf16x8 (&r)[8]) {
+        asm volatile("" ::: "memory");              // the reads stay behind the wait for the copies
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) r[ks] = lds_read_row8(stg + 8192 * slot, c, 2 * ks + hh);
+    };
+    auto lds_reads_done = [] { __builtin_amdgcn_s_waitcnt(0xC07F); };     // lgkmcnt(0): the share may be overwritten
+
     bf16x8 qreg[8], goreg[8];
     float Lq = 0.f, Dq = 0.f;
     {
-        // rows past the end of the group read the group's last row: their scores are all masked
-        // (P = dS = 0 whatever q and dO hold, and a non-finite dO there only reaches dq rows that are
-        // not stored); no select on the loaded values, so the loads are not waited for here
-        const int64_t row = ((int64_t)(gd.tok_base + min(t, Tg - 1)) * a.Hq + head) * 128 + 8 * hh;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            qreg[ks] = *reinterpret_cast<const bf16x8*>(a.q + row + 16 * ks);
-            goreg[ks] = *reinterpret_cast<const bf16x8*>(a.d_o + row + 16 * ks);
+        // whether the forward's rounding residual is valid: one word, read ahead of the copies so that its wait
+        // is theirs
+        const bool use_lo = a.fused_rowsum && a.o_lo != nullptr &&
+                            (a.lo_flag == nullptr || __builtin_amdgcn_readfirstlane((int)*a.lo_flag) != 0);
+        float lse_row = 0.f;
+        if (a.fused_rowsum) {
+            if (valid) lse_row = a.lse[(int64_t)head * T_total + gd.tok_base + t];
+        } else if (valid) {
+            Lq = a.L2[(int64_t)head * T_total + gd.tok_base + t];
+            Dq = a.D[(int64_t)head * T_total + gd.tok_base + t];
+        }
+        stage_rows(a.q, 0);
+        if constexpr (TPR == 2) {
+            stage_rows(a.d_o, 1);
+            wait_vm0();
+            read_rows(0, qreg);
+            read_rows(1, goreg);
+        } else {
+            wait_vm0();
+            read_rows(0, qreg);
+            lds_reads_done();
+            stage_rows(a.d_o, 0);
+            wait_vm0();
+            read_rows(0, goreg);
         }
         if (a.fused_rowsum) {
             // The arithmetic of rowsum_bf16_kernel, operation for operation, so that a backward in one call
@@ -107,20 +161,34 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(BwdArgs a) {
             // (lane `sub` = elements 8 sub .. 8 sub + 7, summed in order by fma) and adds the lanes in an
             // xor-shuffle tree (8, 4, 2, 1).  This lane holds the chunks sub = 2 ks + hh, so the first three
             // levels are sums inside the lane and the last one is the exchange with the row's other lane.
-            const bool use_lo = a.o_lo != nullptr &&
-                                (a.lo_flag == nullptr || __builtin_amdgcn_readfirstlane((int)*a.lo_flag) != 0);
+            bf16x8 oreg[8], lreg[8];
+            lds_reads_done();
+            stage_rows(a.o, 0);
+            if constexpr (TPR == 2) {
+                if (use_lo) stage_rows(a.o_lo, 1);
+                wait_vm0();
+                read_rows(0, oreg);
+                if (use_lo) read_rows(1, lreg);
+            } else {
+                wait_vm0();
+                read_rows(0, oreg);
+                if (use_lo) {
+                    lds_reads_done();
+                    stage_rows(a.o_lo, 0);
+                    wait_vm0();
+                    read_rows(0, lreg);
+                }
+            }
             float ch[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 ov = *reinterpret_cast<const bf16x8*>(a.o + row + 16 * ks);
                 float acc1 = 0.f;
                 if (use_lo) {
-                    const bf16x8 lv = *reinterpret_cast<const bf16x8*>(a.o_lo + row + 16 * ks);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc1 = __builtin_fmaf((float)goreg[ks][e], (float)ov[e] + (float)lv[e], acc1);
+                    for (int e = 0; e < 8; ++e) acc1 = __builtin_fmaf((float)goreg[ks][e], (float)oreg[ks][e] + (float)lreg[ks][e], acc1);
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc1 = __builtin_fmaf((float)goreg[ks][e], (float)ov[e], acc1);
+                    for (int e = 0; e < 8; ++e) acc1 = __builtin_fmaf((float)goreg[ks][e], (float)oreg[ks][e], acc1);
                 }
                 ch[ks] = acc1;
             }
@@ -128,15 +196,15 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(BwdArgs a) {
             const float y0 = x0 + x2, y1 = x1 + x3;
             Dq = pair_sum(y0 + y1);
             if (valid) {
-                Lq = a.lse[(int64_t)head * T_total + gd.tok_base + t] * LOG2E;
+                Lq = lse_row * LOG2E;
                 if (hh == 0) a.L2[(int64_t)head * T_total + gd.tok_base + t] = Lq;
             } else {
                 Dq = 0.f;
             }
-        } else if (valid) {
-            Lq = a.L2[(int64_t)head * T_total + gd.tok_base + t];
-            Dq = a.D[(int64_t)head * T_total + gd.tok_base + t];
         }
+        // the shares overlap the ring slots that the first tile copies (of other waves, too) are about to fill
+        lds_reads_done();
+        __syncthreads();
     }
 
     const int t1 = min(t0 + BM, Tg);
@@ -167,15 +235,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(BwdArgs a) {
         const int row = 4 * (NCH * (w & 3) + u) + (l >> 4);
         voff[u] = row * stride_b + (((l & 15) ^ swz(row)) << 4);
     }
-    auto sgpr64 = [](const void* p) -> uint64_t {
-        const uint64_t b = (uint64_t)(uintptr_t)p;
-        return ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
-               (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
-    };
     const uint64_t kbase_s = sgpr64(kbase), vbase_s = sgpr64(vbase);
-    auto lds_u32 = [](char* p) -> unsigned {
-        return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)p);
-    };
     unsigned m0slot[NSLOT];
 #pragma unroll
     for (int i = 0; i < NSLOT; ++i) m0slot[i] = lds_u32(lds[i]) + 1024u * NCH * (w & 3);
