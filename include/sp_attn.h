@@ -375,6 +375,15 @@ sp_status sp_attn_mfma_ceiling(int32_t lds_operands, const void* a, const void* 
 sp_status sp_attn_probe_atomic_add(float* buf, int64_t rows, int32_t heads, int32_t steps, int32_t n_blocks,
                                    int32_t layout, void* stream);
 
+/* Which workgroup shape a bf16 call on this packing takes for the forward and the dq pass: *rows = 256
+ * or 128 (see sp_attn_set_small_shape_steps below for the rule).  Optionally also the number of 64-key
+ * steps that the workgroups of either tiling run per q head (the quantities the rule compares; the
+ * count for 128-row tiles is in steps of half the rows).  Host arithmetic on the lengths (Section 4.3:
+ * the key ranges of the three terms of its complexity split); no device work; for tools and tests.
+ * Errors as the host checks of sp_attn_fwd_batched. */
+sp_status sp_attn_row_tile(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
+                           const int32_t* resp_lens_flat, int32_t* rows, int64_t* steps_256, int64_t* steps_128);
+
 /* Tuning knob, process-wide (no counterpart in the paper).  The bf16 kernels come in two workgroup
  * shapes: 256 query rows with one workgroup per CU, for long key loops, and 128 rows with two
  * workgroups per CU, whose fixed per-workgroup costs overlap and which execute less work that no row of

@@ -24,7 +24,7 @@ SP_FLAG_RESPONSE_ROWS, SP_FLAG_ACCUMULATE_DKDV = 1, 2
 EXPORTS = ("sp_attn_workspace_bytes", "sp_attn_reserve_bytes", "sp_attn_fwd", "sp_attn_bwd", "sp_attn_fwd_batched",
            "sp_attn_bwd_batched", "sp_attn_bwd_batched_static", "sp_attn_bwd_batched_stages", "sp_attn_fwd_multi", "sp_attn_rope", "sp_attn_rope_qk", "sp_attn_fwd_batched_ex", "sp_attn_bwd_batched_ex",
            "sp_attn_loss_workspace_bytes", "sp_attn_logprob_fwd", "sp_attn_logprob_bwd", "sp_attn_grpo_loss",
-           "sp_attn_segment_table", "sp_attn_mfma_ceiling", "sp_attn_probe_atomic_add", "sp_attn_set_small_shape_steps", "sp_attn_last_error", "sp_attn_version")
+           "sp_attn_segment_table", "sp_attn_row_tile", "sp_attn_mfma_ceiling", "sp_attn_probe_atomic_add", "sp_attn_set_small_shape_steps", "sp_attn_last_error", "sp_attn_version")
 
 _lib = None
 
@@ -91,6 +91,9 @@ def load_library() -> ctypes.CDLL:
     lib.sp_attn_rope_qk.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, ip, ip, ip, i32, ctypes.c_double, ctypes.c_int, vp, sz, vp]
     lib.sp_attn_segment_table.restype = ctypes.c_int
     lib.sp_attn_segment_table.argtypes = [i32, ip, ip, ip, ip, sz, ctypes.POINTER(sz)]
+    lib.sp_attn_row_tile.restype = ctypes.c_int
+    lib.sp_attn_row_tile.argtypes = [i32, ip, ip, ip, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64),
+                                     ctypes.POINTER(ctypes.c_int64)]
     lib.sp_attn_mfma_ceiling.restype = ctypes.c_int
     lib.sp_attn_mfma_ceiling.argtypes = [i32, vp, vp, i32, i32, vp, vp]
     lib.sp_attn_probe_atomic_add.restype = ctypes.c_int
@@ -121,6 +124,17 @@ def sp_attn_segment_table(prompt_lens: Sequence[int], Gs: Sequence[int], resp_le
     buf = (ctypes.c_int32 * n.value)()
     _check(lib.sp_attn_segment_table(*args, buf, n.value, ctypes.byref(n)))
     return list(buf)
+
+
+def sp_attn_row_tile(prompt_lens: Sequence[int], Gs: Sequence[int], resp_lens_flat: Sequence[int]):
+    """(rows, steps_256, steps_128): the workgroup shape (256 or 128 query rows) that a bf16 call on this packing
+    takes, and the 64-key steps per q head of either tiling.  Host arithmetic only."""
+    lib = load_library()
+    rows = ctypes.c_int32(0)
+    s256, s128 = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib.sp_attn_row_tile(len(prompt_lens), _i32(prompt_lens), _i32(Gs), _i32(resp_lens_flat),
+                                ctypes.byref(rows), ctypes.byref(s256), ctypes.byref(s128)))
+    return rows.value, s256.value, s128.value
 
 
 def _i32(xs: Sequence[int]):

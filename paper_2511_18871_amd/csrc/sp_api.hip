@@ -521,6 +521,25 @@ sp_status sp_attn_segment_table(int32_t n_groups, const int32_t* prompt_lens, co
     return SP_OK;
 }
 
+sp_status sp_attn_row_tile(int32_t n_groups, const int32_t* prompt_lens, const int32_t* Gs,
+                           const int32_t* resp_lens_flat, int32_t* rows, int64_t* steps_256, int64_t* steps_128) {
+    g_err[0] = 0;
+    if (!rows) return fail(SP_ERR_INVALID_ARG, "rows is NULL");
+    Layout L;
+    sp_status st = build_table(n_groups, prompt_lens, Gs, resp_lens_flat, L);
+    if (st != SP_OK) return st;
+    sp::Problem p{};
+    p.n_groups = n_groups;
+    p.host_table = L.words.data();
+    int64_t s256, t256, s128, t128;
+    sp::key_steps(p, 256, s256, t256);
+    sp::key_steps(p, 128, s128, t128);
+    *rows = sp::use_small_shape(p) ? 128 : 256;
+    if (steps_256) *steps_256 = s256;
+    if (steps_128) *steps_128 = s128;
+    return SP_OK;
+}
+
 namespace {
 constexpr int MAX_DEVICES = 64;
 std::atomic<void*> g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` on each GPU, 0 = not asked yet

@@ -243,3 +243,50 @@ def test_rope_qk_argument_checks(lib):
     assert f(Hq=0) == B.SP_ERR_INVALID_ARG and f(base=1.0) == B.SP_ERR_INVALID_ARG
     assert f(d=96) == B.SP_ERR_UNSUPPORTED
     assert f(ws=None) == B.SP_ERR_WORKSPACE
+
+
+def test_row_tile_counts_the_key_tiles_that_hold_an_allowed_pair():
+    """sp_attn_row_tile's step counts are, by construction of the key ranges, the number of (row tile, 64-key
+    tile) pairs that hold at least one allowed (query, key) pair: checked against the explicit mask."""
+    import numpy as np
+    from oracle import sp_attn_oracle as orc
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        groups = []
+        for _g in range(int(rng.integers(1, 4))):
+            lp = int(rng.choice([0, 1, 63, 64, 65, 130, int(rng.integers(0, 500))]))
+            lens = [int(rng.choice([0, 1, 32, 64, 100, int(rng.integers(0, 300))])) for _r in range(int(rng.integers(0, 5)))]
+            if lp + sum(lens) == 0:
+                lp = 3
+            groups.append((lp, lens))
+        want = {256: 0, 128: 0}
+        for lp, lens in groups:
+            m = orc.build_mask(lp, lens)
+            T = m.shape[0]
+            for bm in (256, 128):
+                for t0 in range(0, T, bm):
+                    for s0 in range(0, T, 64):
+                        want[bm] += bool(m[t0:t0 + bm, s0:s0 + 64].any())
+        pl = [g[0] for g in groups]; Gs = [len(g[1]) for g in groups]; rl = [x for g in groups for x in g[1]]
+        rows, s256, s128 = B.sp_attn_row_tile(pl, Gs, rl)
+        assert (s256, s128) == (want[256], want[128]), (groups, s256, s128, want)
+        assert rows == (128 if 0.5 * s128 * 1.03 < s256 else 256)
+
+
+def test_row_tile_rule_on_the_bench_workloads_and_the_knob():
+    from paper_2511_18871_amd import workloads as W
+    shape = lambda w: B.sp_attn_row_tile(w.prompt_lens(), w.Gs(), w.resp_lens_flat())[0]
+    # long loops over aligned responses keep the 256-row shape; short or ragged groups take the 128-row one
+    assert [shape(W.config(c)) for c in (2, 3, 4, 5, 6, 7)] == [128, 128, 256, 256, 128, 128]
+    try:
+        B.set_small_shape_steps(0)
+        assert shape(W.config(7)) == 256
+        B.set_small_shape_steps(1 << 20)
+        assert shape(W.config(5)) == 128
+        B.set_small_shape_steps(100)                     # threshold on the mean steps of a 256-row workgroup
+        assert shape(W.config(3)) == 128 and shape(W.config(5)) == 256      # means 55 and 161
+    finally:
+        B.set_small_shape_steps(-1)
+    assert shape(W.config(5)) == 256
+    with pytest.raises(B.SpAttnError):
+        B.sp_attn_row_tile([-1], [1], [5])               # a negative prompt length
