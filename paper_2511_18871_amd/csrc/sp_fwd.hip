@@ -222,16 +222,11 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
         return __builtin_bit_cast(unsigned, v);
     };
 
-    // plain (unpipelined) pieces, used at the ends of the loop and around skipped tiles
+    // the first S = K Q^T, ahead of the pipeline
     auto qk_plain = [&](const char* ldsK, f32x16 (&S)[2]) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
             S[i >> 3] = mfma32(ldK(ldsK, i), qreg[i & 7], (i & 7) == 0 ? zero16 : S[i >> 3]);
-    };
-    auto pv_plain = [&](const char* ldsV, const unsigned (&pbw)[16]) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            oacc[i & 3] = mfma32(cat4(ldV(ldsV, i, 0), ldV(ldsV, i, 1)), pbop(pbw, i >> 3, (i >> 2) & 1), oacc[i & 3]);
     };
     auto mask = [&](int it, f32x16 (&S)[2]) {
         const int s0 = it < total ? tile_at(it) * BN : 0;
@@ -423,7 +418,29 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
     }
     wait_vm0();
     __syncthreads();
-    pv_plain(ldsVb[NB - 1], pbA);               // P of the last (padded) step and its V tile
+    // lane indices re-derived behind an opaque barrier: the addresses of everything behind the loop are
+    // loop-invariant, and hoisted above the main loop they would cost it registers (they were spilled)
+    int lz = l;
+    asm volatile("" : "+v"(lz));
+    {   // P of the last (padded) step and its V tile
+        const int c16z = (lz >> 4) & 1, j16z = lz & 15, hhz = lz >> 5;
+        const char* ldsV = ldsVb[NB - 1];
+        auto ldVz = [&](int i, int half) -> s16x4 {
+            const int col4 = 32 * (i & 3) + 16 * c16z + 4 * (j16z & 3);
+            const int row4 = 32 * (i >> 3) + 16 * ((i >> 2) & 1) + 4 * hhz + (j16z >> 2) + 8 * half;
+            return lds_read_tr4(ldsV, row4, col4);
+        };
+        s16x4 rg[RD][2];
+#pragma unroll
+        for (int i = 0; i < RD - 1; ++i) { rg[i][0] = ldVz(i, 0); rg[i][1] = ldVz(i, 1); }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (i + RD - 1 < 16) { rg[(i + RD - 1) % RD][0] = ldVz(i + RD - 1, 0); rg[(i + RD - 1) % RD][1] = ldVz(i + RD - 1, 1); }
+            oacc[i & 3] = mfma32(cat4(rg[i % RD][0], rg[i % RD][1]), pbop(pbA, i >> 3, (i >> 2) & 1), oacc[i & 3]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 
     // O is normalised by the sum of the ROUNDED weights, the ones V was actually multiplied by:
     // a row dominated by one key then returns that key's V exactly, whatever the reference point.
@@ -438,10 +455,6 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_kernel(FwdArgs a) {      // tw
     // four rows per instruction.  No workgroup barrier: a wave reads back only what it wrote.
     char* const stage = ldsKb[0] + 8192 * w;
     const float inv = 1.0f / lrt;
-    // lane indices re-derived behind an opaque barrier: the addresses below are loop-invariant, and
-    // hoisted above the main loop they would cost it registers
-    int lz = l;
-    asm volatile("" : "+v"(lz));
     auto store_rows = [&, c = lz & 31, hh = lz >> 5, l = lz](__bf16* dst, auto value) {
 #pragma unroll
         for (int db = 0; db < 4; ++db)
